@@ -1,0 +1,192 @@
+/*
+ * gspmd.h -- C ABI of the MI355X (gfx950) per-partition einsum library.
+ *
+ * The library executes the piece of a GSPMD-partitioned program that every
+ * partition runs locally for a Dot/Einsum: the contraction on that partition's
+ * shards (Section 3.2, Section 4), with uneven dimensions padded to a static
+ * shard size and masked (Section 4.1).  Mesh partitions are *virtual*: all of
+ * them live on one GPU; there is no communication.  The one exchange the method
+ * needs -- the AllReduce along a mesh dimension that splits a contracting
+ * dimension (Section 4.2) -- is stood in for by an on-GPU sum of partials.
+ *
+ * Conventions for every entry point
+ *   - Plain C types only.  "host" pointers are read during the call and not
+ *     kept.  "device" pointers are HIP device memory owned by the caller; the
+ *     library never allocates or frees device memory.
+ *   - Device work is enqueued on the given hipStream_t (passed as void*; NULL
+ *     is the default stream) and is complete when that stream is.
+ *   - Every function returns a gspmd_status and never throws, aborts or prints.
+ *     Outputs are written only on GSPMD_OK.
+ *   - Tensors are row-major.  A shard buffer has the STATIC shard shape
+ *     (ceil(D/n) per split dimension, Section 4.1), whatever the partition's
+ *     valid length; the library reads no element at an index >= the valid
+ *     length of any dimension (padding may hold anything, including NaN) and
+ *     writes zeros to the padded part of outputs.
+ */
+#ifndef GSPMD_H_
+#define GSPMD_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  GSPMD_OK = 0,
+  GSPMD_ERR_NULL = 1,            /* a required pointer is NULL */
+  GSPMD_ERR_BAD_MESH = 2,        /* rank/size <= 0, ids not a permutation of 0..P-1 */
+  GSPMD_ERR_BAD_SHARDING = 3,    /* rank mismatch, mesh dim out of range or used twice (Section 3.1) */
+  GSPMD_ERR_PARTITION_RANGE = 4, /* partition id not in the mesh */
+  GSPMD_ERR_BAD_DOT_DIMS = 5,    /* duplicate/out-of-range dims, size mismatch, wrong output shape */
+  GSPMD_ERR_NEEDS_RESHARD = 6,   /* shardings are not one of the communication-free cases (Section 4.5) */
+  GSPMD_ERR_UNSUPPORTED = 7,     /* dtype/layout combination not implemented */
+  GSPMD_ERR_WORKSPACE = 8,       /* workspace missing, misaligned or too small */
+  GSPMD_ERR_DEVICE = 9,          /* a HIP call failed */
+  GSPMD_ERR_BAD_BUFFER = 10      /* row_stride smaller than the shard's last dimension, bad fill count */
+} gspmd_status;
+
+typedef enum { GSPMD_F32 = 0, GSPMD_BF16 = 1 } gspmd_dtype;
+
+/* How a mesh dimension is used by one Dot (Section 3.2 taxonomy applied per mesh dimension,
+ * the cases matched recursively in Section 4.4). */
+typedef enum {
+  GSPMD_AXIS_UNUSED = 0,      /* no operand or output dimension is split on it (replicated) */
+  GSPMD_AXIS_BATCH = 1,       /* the same batch dimension of lhs, rhs and out */
+  GSPMD_AXIS_LHS_FREE = 2,    /* a non-contracting lhs dimension and the matching out dimension */
+  GSPMD_AXIS_RHS_FREE = 3,    /* a non-contracting rhs dimension and the matching out dimension */
+  GSPMD_AXIS_CONTRACTING = 4  /* the same contracting dimension of lhs and rhs; out holds a partial sum */
+} gspmd_axis_class;
+
+/* Device mesh (Section 3.1): `device_ids` is the row-major tensor of partition ids,
+ * prod(shape) entries, a permutation of 0..P-1.  Host memory. */
+typedef struct {
+  int32_t rank;
+  const int64_t* shape;
+  const int64_t* device_ids;
+} gspmd_mesh;
+
+/* mesh_split(tensor, mesh, dims_mapping) of Section 3.1: dims_mapping[i] is the mesh
+ * dimension tensor dimension i is split over, or -1.  Each mesh dimension at most once.
+ * A tiled sharding given as a device tensor of the data's rank is the mesh whose
+ * dimension i maps to data dimension i; a trailing replication dimension stays unmapped. */
+typedef struct {
+  int32_t rank;
+  const int64_t* global_shape;   /* unpartitioned shape, host */
+  const int32_t* dims_mapping;   /* host */
+} gspmd_sharding;
+
+/* Dot dimension numbers (Section 3.2): lhs_batch[i] pairs with rhs_batch[i] and
+ * lhs_contract[i] with rhs_contract[i]; all other dimensions are non-contracting.
+ * Output dimension order: batch, lhs non-contracting, rhs non-contracting. */
+typedef struct {
+  int32_t n_batch;
+  const int32_t* lhs_batch;
+  const int32_t* rhs_batch;
+  int32_t n_contract;
+  const int32_t* lhs_contract;
+  const int32_t* rhs_contract;
+} gspmd_dot_dims;
+
+/* One partition's shard: device pointer to a row-major array of the static shard shape.
+ * row_stride: distance in elements between consecutive indices of the second-to-last
+ * dimension; 0 means dense (= static size of the last dimension).  Outer dimensions are
+ * dense on top of it.  A row_stride that is a multiple of 8 elements together with a
+ * 16-byte aligned pointer selects the MFMA kernels for bf16. */
+typedef struct {
+  void* data;          /* device */
+  int32_t dtype;       /* gspmd_dtype */
+  int64_t row_stride;  /* elements; 0 = dense */
+} gspmd_shard_buf;
+
+const char* gspmd_status_string(int32_t status);
+
+/* Offset(S, d, i) of Section 3.5 with the static shard size of Section 4.1.
+ * For partition `partition_id` and each tensor dimension i:
+ *   shard_size[i] = ceil(D_i / n)          (n = size of the mapped mesh dimension, 1 if unmapped)
+ *   offset[i]     = coord * shard_size[i]  (coord = the partition's position along that mesh dimension)
+ *   valid_len[i]  = clamp(D_i - offset[i], 0, shard_size[i])
+ * offset, valid_len: host arrays of sharding->rank entries; shard_size may be NULL.  Pure host work. */
+int32_t gspmd_shard_bounds(const gspmd_mesh* mesh, const gspmd_sharding* sharding,
+                           int64_t partition_id,
+                           int64_t* offset, int64_t* valid_len, int64_t* shard_size);
+
+/* Per mesh dimension, which communication-free case of the Dot it carries (Section 4.4);
+ * GSPMD_ERR_NEEDS_RESHARD if any mesh dimension fits none (Section 4.5).
+ * axis_class: host array of mesh->rank gspmd_axis_class values. */
+int32_t gspmd_classify_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
+                           const gspmd_sharding* lhs_sh, const gspmd_sharding* rhs_sh,
+                           const gspmd_sharding* out_sh, int32_t* axis_class);
+
+/* Bytes of device workspace gspmd_local_dot (partition_id >= 0) or gspmd_grouped_dot
+ * (partition_id = -1: all partitions) needs for these arguments.  `has_fill` says whether a
+ * fill-count array will be passed.  Pure host work. */
+int32_t gspmd_dot_workspace_bytes(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
+                                  const gspmd_sharding* lhs_sh, const gspmd_sharding* rhs_sh,
+                                  const gspmd_sharding* out_sh, int64_t partition_id,
+                                  int32_t has_fill, int64_t* bytes);
+
+/* The local Dot of one partition (Section 4: the per-partition program of an Einsum whose
+ * mesh dimensions are batch-, lhs-, rhs- or contracting-partitioned):
+ *   out[b.., i.., j..] = sum_c lhs[b.., i.., c..] * rhs[b.., c.., j..]   over the partition's VALID extents,
+ * fp32 accumulation, operands bf16 (out bf16 or f32) or f32 (out f32).
+ * lhs/rhs/out: the partition's shard buffers (static shard shapes under lhs_sh/rhs_sh/out_sh).
+ * Layout: batch dims leading (same order), lhs contracting dims trailing, rhs contracting dims
+ * right after batch; anything else is GSPMD_ERR_UNSUPPORTED.
+ * Positions >= valid length are masked to 0 in both operands along contracting dims and never
+ * read along any dim (Section 4.1); out's padded region is written as 0.
+ * If a mesh dimension is GSPMD_AXIS_CONTRACTING, out must be f32 and receives this
+ * partition's partial sum (to be combined with gspmd_reduce_partials).
+ * lhs_fill (host, nullable): for an lhs with exactly one non-contracting dimension, the number
+ * of occupied positions of that dimension per GLOBAL batch entry (row-major over the global
+ * batch dims); rows at global position >= fill are masked and their out rows are 0
+ * (capacity slots of the mixture-of-experts einsum, Section 5.4).
+ * workspace: device, 256-byte aligned, >= gspmd_dot_workspace_bytes(); contents are
+ * overwritten and must stay untouched until the stream has run the call. */
+int32_t gspmd_local_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
+                        const gspmd_shard_buf* lhs, const gspmd_sharding* lhs_sh,
+                        const gspmd_shard_buf* rhs, const gspmd_sharding* rhs_sh,
+                        const gspmd_shard_buf* out, const gspmd_sharding* out_sh,
+                        int64_t partition_id, const int64_t* lhs_fill,
+                        void* workspace, int64_t workspace_bytes, void* hip_stream);
+
+/* The local Dots of ALL partitions of the mesh in one ragged grouped launch
+ * (single program, many partitions: Section 4).  lhs_shards/rhs_shards/out_shards: host
+ * arrays of P entries indexed by partition id.  Partitions that hold the same data (they
+ * differ only along mesh dimensions the tensor is not split on) may pass the same pointer.
+ * If a mesh dimension is GSPMD_AXIS_CONTRACTING, fp32 partials go to the workspace and are
+ * summed in ascending mesh-coordinate order into the out shard of every member of the reduce
+ * group (the AllReduce of Section 4.2; members may share one buffer, written once); out may
+ * then be bf16 or f32. */
+int32_t gspmd_grouped_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
+                          const gspmd_shard_buf* lhs_shards, const gspmd_sharding* lhs_sh,
+                          const gspmd_shard_buf* rhs_shards, const gspmd_sharding* rhs_sh,
+                          const gspmd_shard_buf* out_shards, const gspmd_sharding* out_sh,
+                          const int64_t* lhs_fill,
+                          void* workspace, int64_t workspace_bytes, void* hip_stream);
+
+/* out[i] = partials[0][i] + partials[1][i] + ... + partials[n_partials-1][i] in fp32, in that
+ * order (the arithmetic of the AllReduce/ReduceScatter of Section 4.2 along a contracting
+ * mesh dimension).  partials: host array of n_partials (1..16) device pointers to dense fp32
+ * arrays of n_elems; out: device, f32 or bf16 (round-to-nearest-even), may alias partials[0]. */
+int32_t gspmd_reduce_partials(const void* const* partials, int32_t n_partials, int64_t n_elems,
+                              void* out, int32_t out_dtype, void* hip_stream);
+
+/* Copy partition `partition_id`'s valid region of a dense global tensor (device) into its
+ * shard buffer (the DynamicSlice of the appendix, Table 9); the shard's padded region is
+ * filled with `pad_bits` (the element's bit pattern, low 16 bits for bf16; padding content is
+ * arbitrary by Section 4.1, so tests poison it). */
+int32_t gspmd_shard_extract(const gspmd_mesh* mesh, const gspmd_sharding* sharding,
+                            int64_t partition_id, const void* global_data,
+                            const gspmd_shard_buf* shard, uint32_t pad_bits, void* hip_stream);
+
+/* Copy the valid region of a shard buffer to its place in a dense global tensor (device):
+ * the DynamicUpdateSlice of the appendix, Table 9. */
+int32_t gspmd_shard_assemble(const gspmd_mesh* mesh, const gspmd_sharding* sharding,
+                             int64_t partition_id, const gspmd_shard_buf* shard,
+                             void* global_data, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GSPMD_H_ */

@@ -1,0 +1,13 @@
+"""MI355X-native per-partition einsum of GSPMD: thin Python binding over libgspmd.so.
+
+Every step of the path runs in the HIP/C++ library; this package only marshals
+arguments (see include/gspmd.h for the contract).  There is no CPU fallback: a
+missing library raises.
+"""
+from .binding import (  # noqa: F401
+    AXIS_BATCH, AXIS_CONTRACTING, AXIS_LHS_FREE, AXIS_RHS_FREE, AXIS_UNUSED,
+    BF16, F32, DotDims, GspmdError, Mesh, Sharding, ShardBuf,
+    classify_dot, dot_workspace_bytes, grouped_dot, library_path, load_library,
+    local_dot, reduce_partials, shard_assemble, shard_bounds, shard_extract,
+    status_string, EXPORTED_SYMBOLS,
+)

@@ -1,0 +1,238 @@
+"""ctypes binding of libgspmd.so: same names as the C ABI, argument marshalling only."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Sequence, Tuple
+
+F32, BF16 = 0, 1
+AXIS_UNUSED, AXIS_BATCH, AXIS_LHS_FREE, AXIS_RHS_FREE, AXIS_CONTRACTING = range(5)
+
+EXPORTED_SYMBOLS = (
+    "gspmd_status_string", "gspmd_shard_bounds", "gspmd_classify_dot", "gspmd_dot_workspace_bytes",
+    "gspmd_local_dot", "gspmd_grouped_dot", "gspmd_reduce_partials", "gspmd_shard_extract",
+    "gspmd_shard_assemble",
+)
+
+
+class GspmdError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: status {status} ({status_string(status)})")
+
+
+class _CMesh(C.Structure):
+    _fields_ = [("rank", C.c_int32), ("shape", C.POINTER(C.c_int64)), ("device_ids", C.POINTER(C.c_int64))]
+
+
+class _CSharding(C.Structure):
+    _fields_ = [("rank", C.c_int32), ("global_shape", C.POINTER(C.c_int64)), ("dims_mapping", C.POINTER(C.c_int32))]
+
+
+class _CDotDims(C.Structure):
+    _fields_ = [("n_batch", C.c_int32), ("lhs_batch", C.POINTER(C.c_int32)), ("rhs_batch", C.POINTER(C.c_int32)),
+                ("n_contract", C.c_int32), ("lhs_contract", C.POINTER(C.c_int32)), ("rhs_contract", C.POINTER(C.c_int32))]
+
+
+class _CShardBuf(C.Structure):
+    _fields_ = [("data", C.c_void_p), ("dtype", C.c_int32), ("row_stride", C.c_int64)]
+
+
+_LIB = None
+
+
+def library_path() -> str:
+    return os.path.join(os.path.dirname(os.path.abspath(__file__)), "libgspmd.so")
+
+
+def load_library():
+    """Load libgspmd.so (built in-tree by paper_2105_04663_amd.build); raises if absent."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = library_path()
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is missing: run `python -m paper_2105_04663_amd.build` (no fallback exists)")
+    lib = C.CDLL(path)
+    lib.gspmd_status_string.restype = C.c_char_p
+    lib.gspmd_status_string.argtypes = [C.c_int32]
+    pm, ps, pd, pb = C.POINTER(_CMesh), C.POINTER(_CSharding), C.POINTER(_CDotDims), C.POINTER(_CShardBuf)
+    pi64, pi32 = C.POINTER(C.c_int64), C.POINTER(C.c_int32)
+    lib.gspmd_shard_bounds.argtypes = [pm, ps, C.c_int64, pi64, pi64, pi64]
+    lib.gspmd_classify_dot.argtypes = [pm, pd, ps, ps, ps, pi32]
+    lib.gspmd_dot_workspace_bytes.argtypes = [pm, pd, ps, ps, ps, C.c_int64, C.c_int32, pi64]
+    lib.gspmd_local_dot.argtypes = [pm, pd, pb, ps, pb, ps, pb, ps, C.c_int64, pi64, C.c_void_p, C.c_int64, C.c_void_p]
+    lib.gspmd_grouped_dot.argtypes = [pm, pd, pb, ps, pb, ps, pb, ps, pi64, C.c_void_p, C.c_int64, C.c_void_p]
+    lib.gspmd_reduce_partials.argtypes = [C.POINTER(C.c_void_p), C.c_int32, C.c_int64, C.c_void_p, C.c_int32, C.c_void_p]
+    lib.gspmd_shard_extract.argtypes = [pm, ps, C.c_int64, C.c_void_p, pb, C.c_uint32, C.c_void_p]
+    lib.gspmd_shard_assemble.argtypes = [pm, ps, C.c_int64, pb, C.c_void_p, C.c_void_p]
+    for name in EXPORTED_SYMBOLS[1:]:
+        getattr(lib, name).restype = C.c_int32
+    _LIB = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load_library().gspmd_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise GspmdError(status, where)
+
+
+def _i64(vals: Sequence[int]):
+    return (C.c_int64 * max(1, len(vals)))(*[int(v) for v in vals])
+
+
+def _i32(vals: Sequence[int]):
+    return (C.c_int32 * max(1, len(vals)))(*[int(v) for v in vals])
+
+
+@dataclass
+class Mesh:
+    """Device mesh: shape and the row-major tensor of partition ids."""
+    shape: Tuple[int, ...]
+    device_ids: Tuple[int, ...]
+
+    def _c(self):
+        self._keep = (_i64(self.shape), _i64(self.device_ids))
+        return _CMesh(len(self.shape), self._keep[0], self._keep[1])
+
+    @property
+    def n_partitions(self) -> int:
+        n = 1
+        for s in self.shape:
+            n *= int(s)
+        return n
+
+
+@dataclass
+class Sharding:
+    """mesh_split annotation: unpartitioned shape and dims_mapping (-1 = not split)."""
+    global_shape: Tuple[int, ...]
+    dims_mapping: Tuple[int, ...]
+
+    def _c(self):
+        self._keep = (_i64(self.global_shape), _i32(self.dims_mapping))
+        rank = len(self.global_shape) if len(self.global_shape) == len(self.dims_mapping) else -1
+        return _CSharding(rank, self._keep[0], self._keep[1])
+
+
+@dataclass
+class DotDims:
+    lhs_batch: Tuple[int, ...]
+    rhs_batch: Tuple[int, ...]
+    lhs_contract: Tuple[int, ...]
+    rhs_contract: Tuple[int, ...]
+
+    def _c(self):
+        self._keep = (_i32(self.lhs_batch), _i32(self.rhs_batch), _i32(self.lhs_contract), _i32(self.rhs_contract))
+        nb = len(self.lhs_batch) if len(self.lhs_batch) == len(self.rhs_batch) else -1
+        nc = len(self.lhs_contract) if len(self.lhs_contract) == len(self.rhs_contract) else -1
+        return _CDotDims(nb, self._keep[0], self._keep[1], nc, self._keep[2], self._keep[3])
+
+
+@dataclass
+class ShardBuf:
+    """A shard in device memory: raw pointer, dtype code and row stride in elements (0 = dense)."""
+    data: int
+    dtype: int
+    row_stride: int = 0
+
+    @staticmethod
+    def of(tensor, row_stride: int = 0) -> "ShardBuf":
+        """Describe a torch tensor's storage (no copy); bf16 and float32 only."""
+        import torch
+        if tensor.dtype == torch.bfloat16:
+            dt = BF16
+        elif tensor.dtype == torch.float32:
+            dt = F32
+        else:
+            raise TypeError("shard buffers are bfloat16 or float32")
+        return ShardBuf(tensor.data_ptr(), dt, row_stride)
+
+    def _c(self):
+        return _CShardBuf(C.c_void_p(self.data), self.dtype, self.row_stride)
+
+
+def _bufs(bufs: Sequence[ShardBuf]):
+    arr = (_CShardBuf * max(1, len(bufs)))()
+    for i, b in enumerate(bufs):
+        arr[i] = b._c()
+    return arr
+
+
+def shard_bounds(mesh: Mesh, sharding: Sharding, partition_id: int):
+    """(offset, valid_len, shard_size) tuples per tensor dimension."""
+    r = max(1, len(sharding.global_shape))
+    off, valid, shard = (C.c_int64 * r)(), (C.c_int64 * r)(), (C.c_int64 * r)()
+    m, s = mesh._c(), sharding._c()
+    _check(load_library().gspmd_shard_bounds(C.byref(m), C.byref(s), int(partition_id), off, valid, shard), "gspmd_shard_bounds")
+    n = len(sharding.global_shape)
+    return tuple(off[:n]), tuple(valid[:n]), tuple(shard[:n])
+
+
+def classify_dot(mesh: Mesh, dims: DotDims, lhs_sh: Sharding, rhs_sh: Sharding, out_sh: Sharding) -> Tuple[int, ...]:
+    cls = (C.c_int32 * max(1, len(mesh.shape)))()
+    m, d, a, b, o = mesh._c(), dims._c(), lhs_sh._c(), rhs_sh._c(), out_sh._c()
+    _check(load_library().gspmd_classify_dot(C.byref(m), C.byref(d), C.byref(a), C.byref(b), C.byref(o), cls), "gspmd_classify_dot")
+    return tuple(cls[:len(mesh.shape)])
+
+
+def dot_workspace_bytes(mesh: Mesh, dims: DotDims, lhs_sh: Sharding, rhs_sh: Sharding, out_sh: Sharding,
+                        partition_id: int = -1, has_fill: bool = False) -> int:
+    n = C.c_int64(0)
+    m, d, a, b, o = mesh._c(), dims._c(), lhs_sh._c(), rhs_sh._c(), out_sh._c()
+    _check(load_library().gspmd_dot_workspace_bytes(C.byref(m), C.byref(d), C.byref(a), C.byref(b), C.byref(o),
+                                                    int(partition_id), int(has_fill), C.byref(n)), "gspmd_dot_workspace_bytes")
+    return int(n.value)
+
+
+def _fill(fill):
+    if fill is None:
+        return None
+    return _i64([int(x) for x in fill])
+
+
+def local_dot(mesh: Mesh, dims: DotDims, lhs: ShardBuf, lhs_sh: Sharding, rhs: ShardBuf, rhs_sh: Sharding,
+              out: ShardBuf, out_sh: Sharding, partition_id: int, lhs_fill=None,
+              workspace: int = 0, workspace_bytes: int = 0, stream: int = 0) -> None:
+    m, d, a, b, o = mesh._c(), dims._c(), lhs_sh._c(), rhs_sh._c(), out_sh._c()
+    la, rb, ob = lhs._c(), rhs._c(), out._c()
+    _check(load_library().gspmd_local_dot(C.byref(m), C.byref(d), C.byref(la), C.byref(a), C.byref(rb), C.byref(b),
+                                          C.byref(ob), C.byref(o), int(partition_id), _fill(lhs_fill),
+                                          C.c_void_p(workspace), int(workspace_bytes), C.c_void_p(stream)), "gspmd_local_dot")
+
+
+def grouped_dot(mesh: Mesh, dims: DotDims, lhs_shards: Sequence[ShardBuf], lhs_sh: Sharding,
+                rhs_shards: Sequence[ShardBuf], rhs_sh: Sharding, out_shards: Sequence[ShardBuf], out_sh: Sharding,
+                lhs_fill=None, workspace: int = 0, workspace_bytes: int = 0, stream: int = 0) -> None:
+    P = mesh.n_partitions
+    if not (len(lhs_shards) == len(rhs_shards) == len(out_shards) == P):
+        raise ValueError("one shard buffer per partition is required")
+    m, d, a, b, o = mesh._c(), dims._c(), lhs_sh._c(), rhs_sh._c(), out_sh._c()
+    _check(load_library().gspmd_grouped_dot(C.byref(m), C.byref(d), _bufs(lhs_shards), C.byref(a), _bufs(rhs_shards), C.byref(b),
+                                            _bufs(out_shards), C.byref(o), _fill(lhs_fill),
+                                            C.c_void_p(workspace), int(workspace_bytes), C.c_void_p(stream)), "gspmd_grouped_dot")
+
+
+def reduce_partials(partials: Sequence[int], n_elems: int, out: int, out_dtype: int, stream: int = 0) -> None:
+    arr = (C.c_void_p * max(1, len(partials)))(*[C.c_void_p(int(p)) for p in partials])
+    _check(load_library().gspmd_reduce_partials(arr, len(partials), int(n_elems), C.c_void_p(out), int(out_dtype),
+                                                C.c_void_p(stream)), "gspmd_reduce_partials")
+
+
+def shard_extract(mesh: Mesh, sharding: Sharding, partition_id: int, global_data: int, shard: ShardBuf,
+                  pad_bits: int = 0, stream: int = 0) -> None:
+    m, s, b = mesh._c(), sharding._c(), shard._c()
+    _check(load_library().gspmd_shard_extract(C.byref(m), C.byref(s), int(partition_id), C.c_void_p(global_data),
+                                              C.byref(b), C.c_uint32(pad_bits & 0xFFFFFFFF), C.c_void_p(stream)), "gspmd_shard_extract")
+
+
+def shard_assemble(mesh: Mesh, sharding: Sharding, partition_id: int, shard: ShardBuf, global_data: int,
+                   stream: int = 0) -> None:
+    m, s, b = mesh._c(), sharding._c(), shard._c()
+    _check(load_library().gspmd_shard_assemble(C.byref(m), C.byref(s), int(partition_id), C.byref(b),
+                                               C.c_void_p(global_data), C.c_void_p(stream)), "gspmd_shard_assemble")

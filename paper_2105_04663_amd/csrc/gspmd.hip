@@ -1,0 +1,377 @@
+// C-ABI entry points of libgspmd (see include/gspmd.h) and the kernel launchers.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstring>
+#include <map>
+#include <vector>
+
+#include "../../include/gspmd.h"
+#include "kernels_basic.h"
+#include "kernels_mfma.h"
+#include "plan.h"
+
+using namespace gspmd;
+
+namespace {
+
+constexpr int64_t kWsAlign = 256;
+
+bool is_dtype(int32_t d) { return d == GSPMD_F32 || d == GSPMD_BF16; }
+
+int32_t check_buf(const gspmd_shard_buf* b) {
+  if (!b) return GSPMD_ERR_NULL;
+  if (!is_dtype(b->dtype)) return GSPMD_ERR_UNSUPPORTED;
+  if (b->row_stride < 0) return GSPMD_ERR_BAD_BUFFER;
+  return GSPMD_OK;
+}
+
+// Assign tile ids for tile edge (bm, bn); returns total tiles or -1 on overflow.
+int64_t assign_tiles(std::vector<Problem>& ps, int bm, int bn) {
+  int64_t t = 0;
+  for (auto& p : ps) {
+    const int64_t tm = (static_cast<int64_t>(p.Ms) + bm - 1) / bm, tn = (static_cast<int64_t>(p.Ns) + bn - 1) / bn;
+    p.tile_begin = static_cast<int32_t>(t);
+    p.tiles_n = static_cast<int32_t>(tn);
+    t += tm * tn;
+    if (t > INT32_MAX) return -1;
+  }
+  return t;
+}
+
+bool mfma_eligible(const std::vector<Problem>& ps, int32_t in_dtype) {
+  if (in_dtype != GSPMD_BF16) return false;
+  for (const auto& p : ps) {
+    if (p.Kv == 0) continue;
+    if ((reinterpret_cast<uintptr_t>(p.A) | reinterpret_cast<uintptr_t>(p.B)) & 15) return false;
+    if ((p.lda & 7) || (p.ldb & 7)) return false;
+  }
+  return true;
+}
+
+// Upload the problem table into the workspace and launch the contraction over all tiles.
+int32_t launch_problems(std::vector<Problem>& ps, int32_t in_dtype, int32_t out_dtype,
+                        void* workspace, int64_t workspace_bytes, hipStream_t stream) {
+  // problems with an empty static output block write nothing
+  ps.erase(std::remove_if(ps.begin(), ps.end(), [](const Problem& p) { return p.Ms == 0 || p.Ns == 0; }), ps.end());
+  if (ps.empty()) return GSPMD_OK;
+  const int64_t table_bytes = static_cast<int64_t>(ps.size()) * sizeof(Problem);
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kWsAlign - 1)) || workspace_bytes < table_bytes)
+    return GSPMD_ERR_WORKSPACE;
+  if (in_dtype == GSPMD_F32 && out_dtype != GSPMD_F32) return GSPMD_ERR_UNSUPPORTED;
+  const bool mfma = mfma_eligible(ps, in_dtype);
+  const int64_t tiles = mfma ? assign_tiles(ps, kMfmaBM, kMfmaBN) : assign_tiles(ps, kGenTile, kGenTile);
+  if (tiles < 0) return GSPMD_ERR_UNSUPPORTED;
+  if (hipMemcpyAsync(workspace, ps.data(), static_cast<size_t>(table_bytes), hipMemcpyHostToDevice, stream) != hipSuccess)
+    return GSPMD_ERR_DEVICE;
+  const Problem* tab = static_cast<const Problem*>(workspace);
+  const int n = static_cast<int>(ps.size());
+  if (mfma) {
+    if (!launch_dot_mfma(tab, n, static_cast<int>(tiles), out_dtype, stream)) return GSPMD_ERR_DEVICE;
+    return GSPMD_OK;
+  }
+  const dim3 grid(static_cast<unsigned>(tiles)), block(256);
+  if (in_dtype == GSPMD_F32)
+    hipLaunchKernelGGL((dot_fallback_kernel<float, float>), grid, block, 0, stream, tab, n);
+  else if (out_dtype == GSPMD_F32)
+    hipLaunchKernelGGL((dot_fallback_kernel<bf16_bits, float>), grid, block, 0, stream, tab, n);
+  else
+    hipLaunchKernelGGL((dot_fallback_kernel<bf16_bits, bf16_bits>), grid, block, 0, stream, tab, n);
+  return hipGetLastError() == hipSuccess ? GSPMD_OK : GSPMD_ERR_DEVICE;
+}
+
+int32_t launch_reduce(const float* const* partials, int n_partials, int64_t rows, int64_t cols, int64_t ld_in,
+                      void* out, int64_t ld_out, int32_t out_dtype, hipStream_t stream) {
+  if (rows == 0 || cols == 0) return GSPMD_OK;
+  PartialPtrs pp;
+  uintptr_t bits = reinterpret_cast<uintptr_t>(out);
+  for (int i = 0; i < kMaxPartials; ++i) pp.p[i] = nullptr;
+  for (int i = 0; i < n_partials; ++i) { pp.p[i] = partials[i]; bits |= reinterpret_cast<uintptr_t>(partials[i]); }
+  const bool vec = !(bits & 15) && !(cols & 3) && !(ld_in & 3) && !(ld_out & 3);
+  const int64_t work = rows * (vec ? cols / 4 : cols);
+  const unsigned blocks = static_cast<unsigned>(std::min<int64_t>((work + 255) / 256, 256 * 32));
+  const dim3 grid(blocks), block(256);
+  if (out_dtype == GSPMD_F32) {
+    if (vec) hipLaunchKernelGGL((reduce_partials_kernel<float, 4>), grid, block, 0, stream, pp, n_partials, rows, cols, ld_in, static_cast<float*>(out), ld_out);
+    else hipLaunchKernelGGL((reduce_partials_kernel<float, 1>), grid, block, 0, stream, pp, n_partials, rows, cols, ld_in, static_cast<float*>(out), ld_out);
+  } else {
+    if (vec) hipLaunchKernelGGL((reduce_partials_kernel<bf16_bits, 4>), grid, block, 0, stream, pp, n_partials, rows, cols, ld_in, static_cast<bf16_bits*>(out), ld_out);
+    else hipLaunchKernelGGL((reduce_partials_kernel<bf16_bits, 1>), grid, block, 0, stream, pp, n_partials, rows, cols, ld_in, static_cast<bf16_bits*>(out), ld_out);
+  }
+  return hipGetLastError() == hipSuccess ? GSPMD_OK : GSPMD_ERR_DEVICE;
+}
+
+bool has_contracting(const gspmd_mesh* mesh, const int32_t* cls) {
+  for (int a = 0; a < mesh->rank; ++a) if (cls[a] == GSPMD_AXIS_CONTRACTING) return true;
+  return false;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* gspmd_status_string(int32_t s) {
+  switch (s) {
+    case GSPMD_OK: return "ok";
+    case GSPMD_ERR_NULL: return "null pointer";
+    case GSPMD_ERR_BAD_MESH: return "bad device mesh";
+    case GSPMD_ERR_BAD_SHARDING: return "bad sharding";
+    case GSPMD_ERR_PARTITION_RANGE: return "partition id out of range";
+    case GSPMD_ERR_BAD_DOT_DIMS: return "bad dot dimension numbers";
+    case GSPMD_ERR_NEEDS_RESHARD: return "shardings need resharding";
+    case GSPMD_ERR_UNSUPPORTED: return "unsupported dtype or layout";
+    case GSPMD_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case GSPMD_ERR_DEVICE: return "HIP error";
+    case GSPMD_ERR_BAD_BUFFER: return "bad shard buffer";
+    default: return "unknown status";
+  }
+}
+
+int32_t gspmd_shard_bounds(const gspmd_mesh* mesh, const gspmd_sharding* sh, int64_t pid,
+                           int64_t* offset, int64_t* valid_len, int64_t* shard_size) {
+  if (!offset || !valid_len) return GSPMD_ERR_NULL;
+  int32_t st = validate_mesh(mesh, nullptr);
+  if (st != GSPMD_OK) return st;
+  if ((st = validate_sharding(mesh, sh)) != GSPMD_OK) return st;
+  Bounds b;
+  if ((st = shard_bounds(mesh, sh, pid, &b)) != GSPMD_OK) return st;
+  for (int i = 0; i < b.rank; ++i) {
+    offset[i] = b.offset[i];
+    valid_len[i] = b.valid[i];
+    if (shard_size) shard_size[i] = b.shard[i];
+  }
+  return GSPMD_OK;
+}
+
+int32_t gspmd_classify_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
+                           const gspmd_sharding* lhs_sh, const gspmd_sharding* rhs_sh,
+                           const gspmd_sharding* out_sh, int32_t* axis_class) {
+  if (!axis_class) return GSPMD_ERR_NULL;
+  DotRoles r;
+  int32_t cls[kMaxRank];
+  const int32_t st = analyse_dot(mesh, dims, lhs_sh, rhs_sh, out_sh, &r, cls);
+  if (st != GSPMD_OK) return st;
+  for (int a = 0; a < mesh->rank; ++a) axis_class[a] = cls[a];
+  return GSPMD_OK;
+}
+
+int32_t gspmd_dot_workspace_bytes(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
+                                  const gspmd_sharding* lhs_sh, const gspmd_sharding* rhs_sh,
+                                  const gspmd_sharding* out_sh, int64_t pid, int32_t /*has_fill*/,
+                                  int64_t* bytes) {
+  if (!bytes) return GSPMD_ERR_NULL;
+  DotRoles r;
+  int32_t cls[kMaxRank];
+  int32_t st = analyse_dot(mesh, dims, lhs_sh, rhs_sh, out_sh, &r, cls);
+  if (st != GSPMD_OK) return st;
+  int64_t P = 1;
+  for (int a = 0; a < mesh->rank; ++a) P *= mesh->shape[a];
+  if (pid < -1 || pid >= P) return GSPMD_ERR_PARTITION_RANGE;
+  int64_t n_prob = 0, partial_bytes = 0;
+  const bool contracting = has_contracting(mesh, cls);
+  for (int64_t p = (pid < 0 ? 0 : pid); p < (pid < 0 ? P : pid + 1); ++p) {
+    int64_t n, e;
+    if ((st = count_partition(mesh, r, lhs_sh, rhs_sh, out_sh, p, &n, &e)) != GSPMD_OK) return st;
+    n_prob += n;
+    if (pid < 0 && contracting) partial_bytes += round_up(e * 4, kWsAlign);
+  }
+  *bytes = round_up(std::max<int64_t>(n_prob, 1) * static_cast<int64_t>(sizeof(Problem)), kWsAlign) + partial_bytes;
+  return GSPMD_OK;
+}
+
+int32_t gspmd_local_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
+                        const gspmd_shard_buf* lhs, const gspmd_sharding* lhs_sh,
+                        const gspmd_shard_buf* rhs, const gspmd_sharding* rhs_sh,
+                        const gspmd_shard_buf* out, const gspmd_sharding* out_sh,
+                        int64_t pid, const int64_t* lhs_fill,
+                        void* workspace, int64_t workspace_bytes, void* hip_stream) {
+  int32_t st;
+  if ((st = check_buf(lhs)) != GSPMD_OK || (st = check_buf(rhs)) != GSPMD_OK || (st = check_buf(out)) != GSPMD_OK) return st;
+  DotRoles r;
+  int32_t cls[kMaxRank];
+  if ((st = analyse_dot(mesh, dims, lhs_sh, rhs_sh, out_sh, &r, cls)) != GSPMD_OK) return st;
+  if (lhs->dtype != rhs->dtype) return GSPMD_ERR_UNSUPPORTED;
+  if (has_contracting(mesh, cls) && out->dtype != GSPMD_F32) return GSPMD_ERR_UNSUPPORTED;
+  std::vector<Problem> ps;
+  int64_t elems = 0;
+  if ((st = plan_partition(mesh, r, lhs, lhs_sh, rhs, rhs_sh, out, out_sh, pid, lhs_fill, nullptr, &ps, &elems)) != GSPMD_OK)
+    return st;
+  for (const auto& p : ps)
+    if ((p.Kv && (!p.A || !p.B)) || !p.C) return GSPMD_ERR_NULL;
+  return launch_problems(ps, lhs->dtype, out->dtype, workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
+}
+
+int32_t gspmd_grouped_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
+                          const gspmd_shard_buf* lhs_shards, const gspmd_sharding* lhs_sh,
+                          const gspmd_shard_buf* rhs_shards, const gspmd_sharding* rhs_sh,
+                          const gspmd_shard_buf* out_shards, const gspmd_sharding* out_sh,
+                          const int64_t* lhs_fill,
+                          void* workspace, int64_t workspace_bytes, void* hip_stream) {
+  if (!lhs_shards || !rhs_shards || !out_shards) return GSPMD_ERR_NULL;
+  DotRoles r;
+  int32_t cls[kMaxRank];
+  int32_t st;
+  if ((st = analyse_dot(mesh, dims, lhs_sh, rhs_sh, out_sh, &r, cls)) != GSPMD_OK) return st;
+  int64_t P = 1;
+  for (int a = 0; a < mesh->rank; ++a) P *= mesh->shape[a];
+  const int32_t in_dtype = lhs_shards[0].dtype, out_dtype = out_shards[0].dtype;
+  for (int64_t p = 0; p < P; ++p) {
+    if ((st = check_buf(&lhs_shards[p])) != GSPMD_OK || (st = check_buf(&rhs_shards[p])) != GSPMD_OK ||
+        (st = check_buf(&out_shards[p])) != GSPMD_OK) return st;
+    if (lhs_shards[p].dtype != in_dtype || rhs_shards[p].dtype != in_dtype || out_shards[p].dtype != out_dtype)
+      return GSPMD_ERR_UNSUPPORTED;
+  }
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const bool contracting = has_contracting(mesh, cls);
+
+  // workspace = [problem table][fp32 partial of partition 0][partial of partition 1]...
+  int64_t need = 0;
+  if ((st = gspmd_dot_workspace_bytes(mesh, dims, lhs_sh, rhs_sh, out_sh, -1, lhs_fill != nullptr, &need)) != GSPMD_OK) return st;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kWsAlign - 1)) || workspace_bytes < need) return GSPMD_ERR_WORKSPACE;
+  int64_t n_bound = 0;
+  std::vector<int64_t> elems(static_cast<size_t>(P), 0);
+  for (int64_t p = 0; p < P; ++p) {
+    int64_t n;
+    if ((st = count_partition(mesh, r, lhs_sh, rhs_sh, out_sh, p, &n, &elems[static_cast<size_t>(p)])) != GSPMD_OK) return st;
+    n_bound += n;
+  }
+  char* partial_base = static_cast<char*>(workspace) + round_up(std::max<int64_t>(n_bound, 1) * static_cast<int64_t>(sizeof(Problem)), kWsAlign);
+  std::vector<float*> partial(static_cast<size_t>(P), nullptr);
+  if (contracting) {
+    int64_t off = 0;
+    for (int64_t p = 0; p < P; ++p) {
+      partial[static_cast<size_t>(p)] = reinterpret_cast<float*>(partial_base + off);
+      off += round_up(elems[static_cast<size_t>(p)] * 4, kWsAlign);
+    }
+  }
+
+  std::vector<Problem> ps;
+  // Partitions that hold the same operands and write the same buffer (replicas along an
+  // unused mesh dimension) need the product only once.
+  std::map<std::array<const void*, 3>, int64_t> done;
+  for (int64_t p = 0; p < P; ++p) {
+    if (!contracting) {
+      std::array<const void*, 3> key = {lhs_shards[p].data, rhs_shards[p].data, out_shards[p].data};
+      if (done.count(key)) continue;
+      done[key] = p;
+    }
+    int64_t e = 0;
+    const size_t before = ps.size();
+    st = plan_partition(mesh, r, &lhs_shards[p], lhs_sh, &rhs_shards[p], rhs_sh, &out_shards[p], out_sh, p, lhs_fill,
+                        contracting ? partial[static_cast<size_t>(p)] : nullptr, &ps, &e);
+    if (st != GSPMD_OK) return st;
+    for (size_t i = before; i < ps.size(); ++i)
+      if ((ps[i].Kv && (!ps[i].A || !ps[i].B)) || !ps[i].C) return GSPMD_ERR_NULL;
+  }
+  st = launch_problems(ps, in_dtype, contracting ? GSPMD_F32 : out_dtype, workspace, workspace_bytes, stream);
+  if (st != GSPMD_OK || !contracting) return st;
+
+  // Sum the partials of each reduce group (partitions that differ only along contracting
+  // mesh dimensions), ascending in mesh position, into every distinct out buffer of the group.
+  std::map<std::vector<int64_t>, std::vector<std::pair<int64_t, int64_t>>> groups;   // key -> (lin pos, pid)
+  for (int64_t p = 0; p < P; ++p) {
+    int64_t coords[kMaxRank];
+    if ((st = mesh_coords(mesh, p, coords)) != GSPMD_OK) return st;
+    std::vector<int64_t> key;
+    int64_t pos = 0;
+    for (int a = 0; a < mesh->rank; ++a) {
+      if (cls[a] == GSPMD_AXIS_CONTRACTING) pos = pos * mesh->shape[a] + coords[a];
+      else key.push_back(coords[a]);
+    }
+    groups[key].emplace_back(pos, p);
+  }
+  for (auto& kv : groups) {
+    auto& members = kv.second;
+    std::sort(members.begin(), members.end());
+    if (members.size() > static_cast<size_t>(kMaxPartials)) return GSPMD_ERR_UNSUPPORTED;
+    std::vector<const float*> ptrs;
+    for (auto& m : members) ptrs.push_back(partial[static_cast<size_t>(m.second)]);
+    Bounds ob;
+    if ((st = shard_bounds(mesh, out_sh, members[0].second, &ob)) != GSPMD_OK) return st;
+    const int64_t cols = ob.shard[ob.rank - 1];
+    const int64_t rows = cols ? elems[static_cast<size_t>(members[0].second)] / cols : 0;
+    std::vector<void*> written;
+    for (auto& m : members) {
+      const gspmd_shard_buf& o = out_shards[m.second];
+      if (std::find(written.begin(), written.end(), o.data) != written.end()) continue;
+      written.push_back(o.data);
+      // outer dims of the out shard are dense over row_stride, so it is a rows x cols matrix
+      const int64_t ld_out = (ob.rank >= 2 && o.row_stride > 0) ? o.row_stride : cols;
+      if (ld_out < cols) return GSPMD_ERR_BAD_BUFFER;
+      if ((st = launch_reduce(ptrs.data(), static_cast<int>(ptrs.size()), rows, cols, cols, o.data, ld_out, o.dtype, stream)) != GSPMD_OK)
+        return st;
+    }
+  }
+  return GSPMD_OK;
+}
+
+int32_t gspmd_reduce_partials(const void* const* partials, int32_t n_partials, int64_t n_elems,
+                              void* out, int32_t out_dtype, void* hip_stream) {
+  if (!partials || !out) return GSPMD_ERR_NULL;
+  if (n_partials < 1 || n_partials > kMaxPartials || n_elems < 0) return GSPMD_ERR_BAD_BUFFER;
+  if (!is_dtype(out_dtype)) return GSPMD_ERR_UNSUPPORTED;
+  for (int i = 0; i < n_partials; ++i) if (!partials[i]) return GSPMD_ERR_NULL;
+  return launch_reduce(reinterpret_cast<const float* const*>(partials), n_partials, 1, n_elems, n_elems, out, n_elems,
+                       out_dtype, static_cast<hipStream_t>(hip_stream));
+}
+
+static int32_t shard_copy(const gspmd_mesh* mesh, const gspmd_sharding* sh, int64_t pid, const void* src_global,
+                          void* dst_global, const gspmd_shard_buf* shard, uint32_t pad_bits, bool extract, void* hip_stream) {
+  int32_t st = validate_mesh(mesh, nullptr);
+  if (st != GSPMD_OK) return st;
+  if ((st = validate_sharding(mesh, sh)) != GSPMD_OK) return st;
+  if ((st = check_buf(shard)) != GSPMD_OK) return st;
+  if (!shard->data || (extract ? !src_global : !dst_global)) return GSPMD_ERR_NULL;
+  Bounds b;
+  if ((st = shard_bounds(mesh, sh, pid, &b)) != GSPMD_OK) return st;
+  CopyDesc d;
+  std::memset(&d, 0, sizeof(d));
+  d.rank = b.rank;
+  int64_t total = 1, goff = 0, gs = 1;
+  for (int i = b.rank - 1; i >= 0; --i) {
+    d.shard[i] = b.shard[i];
+    d.valid[i] = b.valid[i];
+    d.gstride[i] = gs;
+    goff += b.offset[i] * gs;
+    gs *= sh->global_shape[i];
+    total *= b.shard[i];
+  }
+  d.sstride[b.rank - 1] = 1;
+  if (b.rank >= 2) {
+    const int64_t rs = shard->row_stride > 0 ? shard->row_stride : b.shard[b.rank - 1];
+    if (rs < b.shard[b.rank - 1]) return GSPMD_ERR_BAD_BUFFER;
+    d.sstride[b.rank - 2] = rs;
+    for (int i = b.rank - 3; i >= 0; --i) d.sstride[i] = d.sstride[i + 1] * b.shard[i + 1];
+  }
+  if (total == 0) return GSPMD_OK;
+  // A partition wholly in the padding has an offset past the end; it reads/writes nothing
+  // of the global tensor, so keep the base pointer in range.
+  bool any_valid = true;
+  for (int i = 0; i < b.rank; ++i) any_valid = any_valid && b.valid[i] > 0;
+  if (!any_valid) goff = 0;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const unsigned blocks = static_cast<unsigned>(std::min<int64_t>((total + 255) / 256, 256 * 32));
+  const dim3 grid(blocks), block(256);
+  if (shard->dtype == GSPMD_BF16) {
+    typedef bf16_bits T;
+    if (extract) hipLaunchKernelGGL((shard_copy_kernel<T, true>), grid, block, 0, stream, d, static_cast<const T*>(src_global) + goff, static_cast<T*>(shard->data), static_cast<T>(pad_bits & 0xffffu), total);
+    else hipLaunchKernelGGL((shard_copy_kernel<T, false>), grid, block, 0, stream, d, static_cast<const T*>(shard->data), static_cast<T*>(dst_global) + goff, static_cast<T>(0), total);
+  } else {
+    typedef uint32_t T;
+    if (extract) hipLaunchKernelGGL((shard_copy_kernel<T, true>), grid, block, 0, stream, d, static_cast<const T*>(src_global) + goff, static_cast<T*>(shard->data), pad_bits, total);
+    else hipLaunchKernelGGL((shard_copy_kernel<T, false>), grid, block, 0, stream, d, static_cast<const T*>(shard->data), static_cast<T*>(dst_global) + goff, 0u, total);
+  }
+  return hipGetLastError() == hipSuccess ? GSPMD_OK : GSPMD_ERR_DEVICE;
+}
+
+int32_t gspmd_shard_extract(const gspmd_mesh* mesh, const gspmd_sharding* sh, int64_t pid, const void* global_data,
+                            const gspmd_shard_buf* shard, uint32_t pad_bits, void* hip_stream) {
+  return shard_copy(mesh, sh, pid, global_data, nullptr, shard, pad_bits, true, hip_stream);
+}
+
+int32_t gspmd_shard_assemble(const gspmd_mesh* mesh, const gspmd_sharding* sh, int64_t pid, const gspmd_shard_buf* shard,
+                             void* global_data, void* hip_stream) {
+  return shard_copy(mesh, sh, pid, nullptr, global_data, shard, 0, false, hip_stream);
+}
+
+}  // extern "C"

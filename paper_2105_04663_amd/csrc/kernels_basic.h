@@ -1,0 +1,179 @@
+// Device kernels that are not MFMA-shaped: the any-layout fallback contraction (fp32 inputs,
+// or bf16 inputs whose pointers/strides do not allow 16-byte loads), the K-partial sum and the
+// shard <-> global copies.  gfx950 only.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "plan.h"
+
+namespace gspmd {
+
+typedef uint16_t bf16_bits;
+
+__device__ __forceinline__ float bf16_to_float(bf16_bits b) {
+  return __uint_as_float(static_cast<uint32_t>(b) << 16);
+}
+
+// round-to-nearest-even; NaN stays NaN (quiet bit forced so the payload cannot round to Inf)
+__device__ __forceinline__ bf16_bits float_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<bf16_bits>((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return static_cast<bf16_bits>(u >> 16);
+}
+
+template <typename T> __device__ __forceinline__ float load_as_float(const T* p);
+template <> __device__ __forceinline__ float load_as_float<float>(const float* p) { return *p; }
+template <> __device__ __forceinline__ float load_as_float<bf16_bits>(const bf16_bits* p) { return bf16_to_float(*p); }
+
+template <typename T> __device__ __forceinline__ void store_from_float(T* p, float v);
+template <> __device__ __forceinline__ void store_from_float<float>(float* p, float v) { *p = v; }
+template <> __device__ __forceinline__ void store_from_float<bf16_bits>(bf16_bits* p, float v) { *p = float_to_bf16(v); }
+
+// Which problem owns output tile `tile`: the last entry whose tile_begin <= tile.
+__device__ __forceinline__ int find_problem(const Problem* __restrict__ tab, int n_prob, int tile) {
+  int lo = 0, hi = n_prob - 1;
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (tab[mid].tile_begin <= tile) lo = mid; else hi = mid - 1;
+  }
+  return lo;
+}
+
+constexpr int kGenTile = 64;   // output tile edge of the fallback kernel
+constexpr int kGenBK = 16;
+
+// Fallback contraction: 64x64 output tile per workgroup, 4x4 outputs per thread, fp32 FMA.
+// Every load is predicated on the valid extents (masked positions contribute 0 and are never
+// read); stores cover the static extents and write 0 outside the valid region.
+template <typename TIn, typename TOut>
+__global__ __launch_bounds__(256) void dot_fallback_kernel(const Problem* __restrict__ tab, int n_prob) {
+  __shared__ float As[kGenBK][kGenTile + 4];   // [k][m]
+  __shared__ float Bs[kGenBK][kGenTile + 4];   // [k][n]
+  const int tile = blockIdx.x;
+  const Problem P = tab[find_problem(tab, n_prob, tile)];
+  const int local = tile - P.tile_begin;
+  const int m0 = (local / P.tiles_n) * kGenTile, n0 = (local % P.tiles_n) * kGenTile;
+  const TIn* __restrict__ A = static_cast<const TIn*>(P.A);
+  const TIn* __restrict__ B = static_cast<const TIn*>(P.B);
+  TOut* __restrict__ C = static_cast<TOut*>(P.C);
+  const int t = threadIdx.x, tx = t & 15, ty = t >> 4;
+  float acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+
+  if (m0 < P.Mv && n0 < P.Nv) {
+    const int am = t >> 2, ak = (t & 3) * 4;     // A: row am, 4 consecutive k
+    const int bk = t >> 4, bn = (t & 15) * 4;    // B: row bk, 4 consecutive n
+    for (int k0 = 0; k0 < P.Kv; k0 += kGenBK) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int m = m0 + am, k = k0 + ak + j;
+        As[ak + j][am] = (m < P.Mv && k < P.Kv) ? load_as_float<TIn>(A + static_cast<int64_t>(m) * P.lda + k) : 0.f;
+        const int kk = k0 + bk, n = n0 + bn + j;
+        Bs[bk][bn + j] = (kk < P.Kv && n < P.Nv) ? load_as_float<TIn>(B + static_cast<int64_t>(kk) * P.ldb + n) : 0.f;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int k = 0; k < kGenBK; ++k) {
+        float a[4], b[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { a[i] = As[k][ty * 4 + i]; b[i] = Bs[k][tx * 4 + i]; }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+      }
+      __syncthreads();
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int m = m0 + ty * 4 + i;
+    if (m >= P.Ms) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int n = n0 + tx * 4 + j;
+      if (n >= P.Ns) continue;
+      const float v = (m < P.Mv && n < P.Nv) ? acc[i][j] : 0.f;
+      store_from_float<TOut>(C + static_cast<int64_t>(m) * P.ldc + n, v);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Sum of K-partials (the arithmetic of the AllReduce along a contracting mesh dimension).
+// ---------------------------------------------------------------------------------------
+constexpr int kMaxPartials = 16;
+struct PartialPtrs { const float* p[kMaxPartials]; };
+
+// rows x cols fp32 partials with leading dimension ld_in -> out with leading dimension ld_out.
+// VEC = 4: cols, both leading dimensions and all pointers allow 16-byte (fp32) accesses.
+template <typename TOut, int VEC>
+__global__ __launch_bounds__(256) void reduce_partials_kernel(PartialPtrs ptrs, int n_partials,
+                                                              int64_t rows, int64_t cols, int64_t ld_in,
+                                                              TOut* __restrict__ out, int64_t ld_out) {
+  const int64_t cols_v = cols / VEC;
+  const int64_t total = rows * cols_v;
+  for (int64_t i = blockIdx.x * static_cast<int64_t>(blockDim.x) + threadIdx.x; i < total;
+       i += static_cast<int64_t>(gridDim.x) * blockDim.x) {
+    const int64_t r = i / cols_v, c = (i - r * cols_v) * VEC;
+    float acc[VEC];
+    if constexpr (VEC == 4) {
+      const float4 v = *reinterpret_cast<const float4*>(ptrs.p[0] + r * ld_in + c);
+      acc[0] = v.x; acc[1] = v.y; acc[2] = v.z; acc[3] = v.w;
+      for (int p = 1; p < n_partials; ++p) {   // fixed ascending order: deterministic
+        const float4 w = *reinterpret_cast<const float4*>(ptrs.p[p] + r * ld_in + c);
+        acc[0] += w.x; acc[1] += w.y; acc[2] += w.z; acc[3] += w.w;
+      }
+      if constexpr (sizeof(TOut) == 4) {
+        *reinterpret_cast<float4*>(out + r * ld_out + c) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+      } else {
+        ushort4 o;
+        o.x = float_to_bf16(acc[0]); o.y = float_to_bf16(acc[1]);
+        o.z = float_to_bf16(acc[2]); o.w = float_to_bf16(acc[3]);
+        *reinterpret_cast<ushort4*>(out + r * ld_out + c) = o;
+      }
+    } else {
+      acc[0] = ptrs.p[0][r * ld_in + c];
+      for (int p = 1; p < n_partials; ++p) acc[0] += ptrs.p[p][r * ld_in + c];
+      store_from_float<TOut>(out + r * ld_out + c, acc[0]);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Shard <-> global copies (DynamicSlice / DynamicUpdateSlice of the appendix).
+// ---------------------------------------------------------------------------------------
+struct CopyDesc {
+  int32_t rank;
+  int64_t shard[kMaxRank];     // static shard shape
+  int64_t valid[kMaxRank];
+  int64_t sstride[kMaxRank];   // shard strides (elements)
+  int64_t gstride[kMaxRank];   // global strides (elements), offset already folded into the base
+};
+
+// EXTRACT: shard[idx] = idx valid ? global[idx] : pad.   !EXTRACT: global[idx] = shard[idx] for valid idx.
+template <typename T, bool EXTRACT>
+__global__ __launch_bounds__(256) void shard_copy_kernel(CopyDesc d, const T* __restrict__ src,
+                                                         T* __restrict__ dst, T pad, int64_t total) {
+  for (int64_t i = blockIdx.x * static_cast<int64_t>(blockDim.x) + threadIdx.x; i < total;
+       i += static_cast<int64_t>(gridDim.x) * blockDim.x) {
+    int64_t rem = i, so = 0, go = 0;
+    bool ok = true;
+    for (int k = d.rank - 1; k >= 0; --k) {
+      const int64_t x = rem % d.shard[k];
+      rem /= d.shard[k];
+      so += x * d.sstride[k];
+      go += x * d.gstride[k];
+      ok = ok && (x < d.valid[k]);
+    }
+    if (EXTRACT) dst[so] = ok ? src[go] : pad;
+    else if (ok) dst[go] = src[so];
+  }
+}
+
+}  // namespace gspmd

@@ -1,0 +1,294 @@
+"""GPU parity: the HIP path through the C ABI against the fp64 CPU oracle, element by element.
+
+Tolerances (benchmark definition): bf16 operands with fp32 accumulation must satisfy
+max |err| <= 1e-2 * (|ref| + 1) and relative Frobenius error <= 5e-3; the fp32 tiny config
+additionally relative Frobenius <= 1e-5; integer-valued inputs with fp32 output are bit-exact.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2105_04663_amd as g
+import workloads as wl
+from oracle import bounds as ob
+from oracle import dot as od
+from tests.harness import Staged, to_f64
+
+pytestmark = pytest.mark.gpu
+
+MAX_SCALED, MAX_FRO = 1e-2, 5e-3
+
+
+def widen(w, arr):
+    return wl.bf16_bits_to_f64(arr) if w.dtype == "bf16" else arr.astype(np.float64)
+
+
+def check(got, ref, fro_tol=MAX_FRO, exact=False, what=""):
+    assert got.shape == ref.shape, what
+    if exact:
+        assert np.array_equal(got, ref), what
+        return
+    assert np.isfinite(got).all(), what
+    s, f = od.error_metrics(got, ref)
+    assert s <= MAX_SCALED and f <= fro_tol, f"{what}: scaled {s:.3e} fro {f:.3e}"
+
+
+def oracle_global(w, lhs, rhs, fill=None):
+    a, b = widen(w, lhs), widen(w, rhs)
+    if fill is not None:
+        a = od.apply_fill(a, w.lhs_batch, [d for d in range(a.ndim) if d not in w.lhs_batch and d not in w.lhs_contract][0], fill)
+    return od.dot_general(a, b, w.lhs_batch, w.rhs_batch, w.lhs_contract, w.rhs_contract)
+
+
+def compare_all_shards(st, w, out_global, **kw):
+    for pid in range(st.P):
+        want = od.expected_out_shard(out_global, w.mesh_shape, w.device_ids, w.out_map, pid)
+        check(st.out_shard(pid), want, what=f"{w.name} pid {pid}", **kw)   # includes pad == 0
+
+
+# --------------------------------------------------------------------------- config 1
+@pytest.mark.parametrize("mode", ["local", "grouped"])
+@pytest.mark.parametrize("row_align", [0, 8])
+def test_config1_tiny_fp32(mode, row_align):
+    w = wl.tiny_1d()
+    lhs, rhs = w.draw_lhs(), w.draw_rhs()
+    out = oracle_global(w, lhs, rhs)
+    st = Staged(w, lhs, rhs, row_align=row_align)
+    for pid in range(4):
+        off, valid, shard = g.shard_bounds(st.mesh, st.out_sh, pid)
+        assert (off, valid, shard) == ob.shard_bounds(w.mesh_shape, w.device_ids, w.out_shape, w.out_map, pid)
+    if mode == "local":
+        for pid in range(4):
+            st.run_local(pid)
+    else:
+        st.run_grouped()
+    compare_all_shards(st, w, out, fro_tol=1e-5)
+    check(st.assemble(), out, fro_tol=1e-5, what="reassembled")
+
+
+# --------------------------------------------------------------------------- MFMA path, ragged
+RAGGED = [  # M, K, N : several 256-tiles and ragged tails in every dimension
+    (600, 200, 520), (257, 64, 255), (256, 512, 256), (1, 8, 1), (300, 1000, 264), (513, 72, 1030), (40, 4104, 24),
+]
+
+
+@pytest.mark.parametrize("M,K,N", RAGGED)
+@pytest.mark.parametrize("out_dtype", ["bf16", "f32"])
+def test_single_partition_ragged(M, K, N, out_dtype):
+    w = wl.mesh2d(M=M, K=K, N=N, X=1, Y=1, cfg=7)
+    lhs, rhs = wl.draw_normal_bf16(1, (M, K)), wl.draw_normal_bf16(2, (K, N), 0.05)
+    st = Staged(w, lhs, rhs, row_align=8, out_dtype=out_dtype)
+    st.run_local(0)
+    compare_all_shards(st, w, oracle_global(w, lhs, rhs))
+
+
+@pytest.mark.parametrize("M,K,N", [(300, 200, 264), (512, 1024, 256), (37, 1000, 70)])
+@pytest.mark.parametrize("row_align", [8, 0])
+def test_integer_inputs_bit_exact(M, K, N, row_align):
+    # products and partial sums of integers in [-8, 8] over K <= 1024 are exact in fp32, so any
+    # accumulation order must give the oracle's value bit for bit
+    w = wl.mesh2d(M=M, K=K, N=N, X=1, Y=1, cfg=7)
+    lhs, rhs = wl.draw_small_int_bf16(3, (M, K)), wl.draw_small_int_bf16(4, (K, N))
+    st = Staged(w, lhs, rhs, row_align=row_align, out_dtype="f32")
+    st.run_local(0)
+    compare_all_shards(st, w, oracle_global(w, lhs, rhs), exact=True)
+
+
+@pytest.mark.parametrize("row_align", [8, 0])
+def test_poisoned_padding_does_not_leak(row_align):
+    # uneven in every dim of a 2x3 mesh with K split too would need a reduce; here M, N uneven + K tail
+    ids = np.random.default_rng(9).permutation(6).tolist()
+    w = wl.mesh2d(M=601, K=203, N=530, X=2, Y=3, cfg=7, device_ids=ids)
+    lhs, rhs = wl.draw_small_int_bf16(5, w.lhs_shape), wl.draw_small_int_bf16(6, w.rhs_shape)
+    outs = {}
+    for poison in ("nan", "huge", None):
+        st = Staged(w, lhs, rhs, row_align=row_align, poison_bits=poison, out_dtype="f32")
+        st.run_grouped()
+        outs[poison] = [st.out_shard(p) for p in range(st.P)]
+    ref = oracle_global(w, lhs, rhs)
+    for p in range(6):
+        want = od.expected_out_shard(ref, w.mesh_shape, w.device_ids, w.out_map, p)
+        for poison in outs:
+            assert np.array_equal(outs[poison][p], want), (poison, p)
+
+
+# --------------------------------------------------------------------------- contracting split
+@pytest.mark.parametrize("M,K,N,P", [(300, 1000, 264, 4), (9, 30, 7, 4), (256, 2048, 512, 2), (64, 5, 64, 4)])
+@pytest.mark.parametrize("out_dtype", ["f32", "bf16"])
+def test_contracting_split_grouped_reduce(M, K, N, P, out_dtype):
+    w = wl.ksplit(M=M, K=K, N=N, P=P)
+    lhs, rhs = wl.draw_normal_bf16(1, w.lhs_shape), wl.draw_normal_bf16(2, w.rhs_shape, 0.05)
+    assert g.classify_dot(g.Mesh(w.mesh_shape, w.device_ids), g.DotDims((), (), (1,), (0,)),
+                          g.Sharding(w.lhs_shape, w.lhs_map), g.Sharding(w.rhs_shape, w.rhs_map),
+                          g.Sharding(w.out_shape, w.out_map)) == (g.AXIS_CONTRACTING,)
+    st = Staged(w, lhs, rhs, row_align=8, out_dtype=out_dtype)
+    st.run_grouped()
+    ref = oracle_global(w, lhs, rhs)
+    for pid in range(P):      # AllReduce semantics: every member holds the full sum
+        check(st.out_shard(pid), ref, what=f"pid {pid}")
+
+
+def test_contracting_split_local_partials_and_reduce():
+    w = wl.ksplit(M=300, K=1000, N=264, P=4)
+    lhs, rhs = wl.draw_small_int_bf16(1, w.lhs_shape), wl.draw_small_int_bf16(2, w.rhs_shape)
+    st = Staged(w, lhs, rhs, row_align=8, out_dtype="f32", share_replicas=False)
+    dims = (w.lhs_batch, w.rhs_batch, w.lhs_contract, w.rhs_contract)
+    a, b = widen(w, lhs), widen(w, rhs)
+    for pid in range(4):
+        st.run_local(pid)
+        want = od.expected_partial(a, b, dims, w.mesh_shape, w.device_ids, w.lhs_map, w.rhs_map, pid)
+        check(st.out_shard(pid), want, exact=True, what=f"partial {pid}")
+    # bf16 out of a partial is refused: a partial sum must stay fp32 until reduced
+    st2 = Staged(w, lhs, rhs, row_align=8, out_dtype="bf16")
+    with pytest.raises(g.GspmdError) as e:
+        st2.run_local(0)
+    assert e.value.status == 7
+    # the public reduce call on the four partials
+    parts = [st.out[p][1] for p in range(4)]
+    n = 300 * 264
+    out = torch.empty(n, dtype=torch.float32, device="cuda")
+    g.reduce_partials([t.data_ptr() for t in parts], n, out.data_ptr(), g.F32, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_f64(out).reshape(300, 264), od.dot_general(a, b, *dims))
+    outb = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+    g.reduce_partials([t.data_ptr() for t in parts], n, outb.data_ptr(), g.BF16, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert torch.equal(outb, out.to(torch.bfloat16))     # round-to-nearest-even of the fp32 sum
+
+
+# --------------------------------------------------------------------------- MoE fill counts
+@pytest.mark.parametrize("mode", ["local", "grouped"])
+@pytest.mark.parametrize("E,C,M,H,align", [(3, 300, 256, 520, 8), (2, 64, 40, 33, 0)])
+def test_moe_fill_counts(mode, E, C, M, H, align):
+    w = wl.moe(E=E, C=C, M=M, H=H)
+    fill = w.draw_fill()
+    # rows beyond the fill count are NOT zero in the staged input here: the mask must do it
+    lhs, rhs = wl.draw_normal_bf16(1, w.lhs_shape), wl.draw_normal_bf16(2, w.rhs_shape, 0.05)
+    st = Staged(w, lhs, rhs, row_align=align)
+    if mode == "local":
+        st.run_local(0, fill=fill)
+    else:
+        st.run_grouped(fill=fill)
+    ref = oracle_global(w, lhs, rhs, fill=fill)
+    compare_all_shards(st, w, ref)
+    got = st.out_shard(0)
+    for e in range(E):
+        assert not got[e, fill[e]:].any()
+
+
+def test_moe_experts_sharded_over_mesh():
+    # E split over 2 partitions (batch-partitioned mesh dim), uneven: 3 experts -> shards of 2, last valid 1
+    w = wl.moe(E=3, C=200, M=128, H=264)
+    w.mesh_shape, w.device_ids = (2,), (1, 0)
+    fill = w.draw_fill()
+    lhs, rhs = wl.draw_normal_bf16(1, w.lhs_shape), wl.draw_normal_bf16(2, w.rhs_shape, 0.05)
+    st = Staged(w, lhs, rhs, row_align=8)
+    assert g.classify_dot(st.mesh, st.dims, st.lhs_sh, st.rhs_sh, st.out_sh) == (g.AXIS_BATCH,)
+    st.run_grouped(fill=fill)
+    ref = oracle_global(w, lhs, rhs, fill=fill)
+    compare_all_shards(st, w, ref)
+    check(st.assemble(), ref, what="reassembled")
+
+
+# --------------------------------------------------------------------------- nested mesh
+@pytest.mark.parametrize("align", [8, 0])
+@pytest.mark.parametrize("mode", ["local", "grouped"])
+def test_nested_mesh_uneven_permuted_ids(align, mode):
+    ids = np.random.default_rng(21).permutation(12).tolist()
+    w = wl.mesh2d(M=1001, K=300, N=1100, X=3, Y=4, cfg=7, device_ids=ids)
+    lhs, rhs = wl.draw_normal_bf16(1, w.lhs_shape), wl.draw_normal_bf16(2, w.rhs_shape, 0.05)
+    st = Staged(w, lhs, rhs, row_align=align)
+    assert g.classify_dot(st.mesh, st.dims, st.lhs_sh, st.rhs_sh, st.out_sh) == (g.AXIS_LHS_FREE, g.AXIS_RHS_FREE)
+    if mode == "grouped":
+        st.run_grouped()
+    else:
+        for pid in range(12):
+            st.run_local(pid)
+    ref = oracle_global(w, lhs, rhs)
+    compare_all_shards(st, w, ref)
+    check(st.assemble(), ref, what="reassembled")
+
+
+def test_partition_wholly_in_padding_writes_zeros():
+    # 5 rows over 4 partitions: shard 2, the last partition has no valid row
+    w = wl.mesh2d(M=5, K=64, N=40, X=4, Y=1, cfg=7)
+    lhs, rhs = wl.draw_normal_bf16(1, w.lhs_shape), wl.draw_normal_bf16(2, w.rhs_shape)
+    st = Staged(w, lhs, rhs, row_align=8)
+    st.run_grouped()
+    ref = oracle_global(w, lhs, rhs)
+    compare_all_shards(st, w, ref)
+    assert not st.out_shard(3).any()
+
+
+# --------------------------------------------------------------------------- rank-polymorphic dots
+def _generic(lhs_shape, rhs_shape, lb, rb, lc, rc, mesh_shape, lmap, rmap, omap, dtype="bf16", out_dtype="bf16"):
+    w = wl.DotWorkload(name="generic", cfg=8, dtype=dtype, out_dtype=out_dtype, lhs_shape=lhs_shape, rhs_shape=rhs_shape,
+                       lhs_batch=lb, rhs_batch=rb, lhs_contract=lc, rhs_contract=rc, mesh_shape=mesh_shape,
+                       device_ids=tuple(range(int(np.prod(mesh_shape)))), lhs_map=lmap, rhs_map=rmap, out_map=omap)
+    return w
+
+
+@pytest.mark.parametrize("align", [8, 0])
+def test_bsm_mh_two_free_dims_sharded_batch_and_hidden(align):
+    # BSM,MH->BSH on a (2,2) mesh: B on X (uneven 3/2), H on Y
+    w = _generic((3, 50, 64), (64, 72), (), (), (2,), (0,), (2, 2), (0, -1, -1), (-1, 1), (0, -1, 1))
+    lhs, rhs = wl.draw_normal_bf16(1, w.lhs_shape), wl.draw_normal_bf16(2, w.rhs_shape, 0.05)
+    st = Staged(w, lhs, rhs, row_align=align)
+    st.run_grouped()
+    ref = oracle_global(w, lhs, rhs)
+    compare_all_shards(st, w, ref)
+    check(st.assemble(), ref, what="reassembled")
+
+
+def test_sequence_dim_sharded_unevenly_needs_per_row_problems():
+    # S (the inner of two lhs free dims) split unevenly: the padded rows sit inside the flattened
+    # row range, so the plan falls back to one problem per B index
+    w = _generic((3, 51, 64), (64, 72), (), (), (2,), (0,), (2,), (-1, 0, -1), (-1, -1), (-1, 0, -1))
+    lhs, rhs = wl.draw_normal_bf16(1, w.lhs_shape), wl.draw_normal_bf16(2, w.rhs_shape, 0.05)
+    st = Staged(w, lhs, rhs, row_align=8)
+    st.run_grouped()
+    ref = oracle_global(w, lhs, rhs)
+    compare_all_shards(st, w, ref)
+
+
+def test_two_contracting_dims_and_batch_fp32():
+    # b i c1 c2 , b c1 c2 j -> b i j   with c1 split over the mesh (contracting) and fp32 data
+    w = _generic((2, 9, 4, 6), (2, 4, 6, 11), (0,), (0,), (2, 3), (1, 2), (2,), (-1, -1, 0, -1), (-1, 0, -1, -1),
+                 (-1, -1, -1), dtype="f32", out_dtype="f32")
+    lhs, rhs = wl.draw_uniform_f32(1, w.lhs_shape), wl.draw_uniform_f32(2, w.rhs_shape)
+    st = Staged(w, lhs, rhs, row_align=0)
+    st.run_grouped()
+    ref = oracle_global(w, lhs, rhs)
+    for pid in range(2):
+        check(st.out_shard(pid), ref, fro_tol=1e-5)
+
+
+def test_needs_reshard_and_bad_arguments_on_device_calls():
+    w = wl.mesh2d(M=64, K=64, N=64, X=2, Y=2, cfg=7)
+    lhs, rhs = wl.draw_normal_bf16(1, w.lhs_shape), wl.draw_normal_bf16(2, w.rhs_shape)
+    st = Staged(w, lhs, rhs)
+    base, n = st.workspace(0)
+    bad_out = g.Sharding(w.out_shape, (1, 0))        # output split the other way round: needs resharding
+    with pytest.raises(g.GspmdError) as e:
+        g.local_dot(st.mesh, st.dims, st.lhs[0][0], st.lhs_sh, st.rhs[0][0], st.rhs_sh, st.out[0][0], bad_out, 0, None, base, n, 0)
+    assert e.value.status == 6
+    with pytest.raises(g.GspmdError) as e:           # workspace too small / missing
+        g.local_dot(st.mesh, st.dims, st.lhs[0][0], st.lhs_sh, st.rhs[0][0], st.rhs_sh, st.out[0][0], st.out_sh, 0, None, 0, 0, 0)
+    assert e.value.status == 8
+    with pytest.raises(g.GspmdError) as e:           # misaligned workspace
+        g.local_dot(st.mesh, st.dims, st.lhs[0][0], st.lhs_sh, st.rhs[0][0], st.rhs_sh, st.out[0][0], st.out_sh, 0, None, base + 8, n, 0)
+    assert e.value.status == 8
+    with pytest.raises(g.GspmdError) as e:
+        g.local_dot(st.mesh, st.dims, st.lhs[0][0], st.lhs_sh, st.rhs[0][0], st.rhs_sh, st.out[0][0], st.out_sh, 4, None, base, n, 0)
+    assert e.value.status == 4
+
+
+def test_deterministic_across_runs():
+    w = wl.ksplit(M=300, K=1000, N=264, P=4)
+    lhs, rhs = wl.draw_normal_bf16(1, w.lhs_shape), wl.draw_normal_bf16(2, w.rhs_shape, 0.05)
+    st = Staged(w, lhs, rhs, out_dtype="f32")
+    outs = []
+    for _ in range(3):
+        st.run_grouped()
+        outs.append(st.out_shard(0).copy())
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])

@@ -1,0 +1,167 @@
+"""CPU-side tests of the C ABI: the library loads, exports what the header declares, and its
+host index math (bounds, classification, error codes) agrees with the oracle.  No kernels run."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+from hypothesis import given, settings, strategies as st
+
+import paper_2105_04663_amd as g
+from oracle import bounds as ob
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    text = open(os.path.join(ROOT, "include", "gspmd.h")).read()
+    declared = set(re.findall(r"\b(gspmd_[a-z_]+)\s*\(", text))
+    assert declared == set(g.EXPORTED_SYMBOLS)
+    lib = g.load_library()
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert g.status_string(0) == "ok"
+
+
+@st.composite
+def mesh_and_tensor(draw):
+    mrank = draw(st.integers(1, 3))
+    mshape = tuple(draw(st.integers(1, 4)) for _ in range(mrank))
+    P = int(np.prod(mshape))
+    ids = tuple(draw(st.permutations(list(range(P)))))
+    trank = draw(st.integers(1, 4))
+    shape = tuple(draw(st.integers(0, 40)) for _ in range(trank))
+    axes = draw(st.permutations(list(range(mrank))))
+    dims = draw(st.permutations(list(range(trank))))
+    mapping = [-1] * trank
+    for a, d in zip(axes[:draw(st.integers(0, min(mrank, trank)))], dims):
+        mapping[d] = a
+    return mshape, ids, shape, tuple(mapping)
+
+
+@settings(max_examples=300, deadline=None)
+@given(mesh_and_tensor())
+def test_bounds_bit_exact_against_oracle(case):
+    mshape, ids, shape, mapping = case
+    mesh, sh = g.Mesh(mshape, ids), g.Sharding(shape, mapping)
+    for pid in range(len(ids)):
+        assert g.shard_bounds(mesh, sh, pid) == ob.shard_bounds(mshape, ids, shape, mapping, pid)
+
+
+def test_bounds_large_values_stay_exact():
+    mesh = g.Mesh((7, 3), tuple(range(21)))
+    shape, mapping = ((1 << 40) + 5, (1 << 33) + 1), (0, 1)
+    for pid in (0, 5, 20):
+        assert g.shard_bounds(mesh, g.Sharding(shape, mapping), pid) == ob.shard_bounds((7, 3), tuple(range(21)), shape, mapping, pid)
+
+
+@pytest.mark.parametrize("mesh,sh,pid,status", [
+    (g.Mesh((2, 2), (0, 1, 2, 2)), g.Sharding((4,), (0,)), 0, 2),      # ids not a permutation
+    (g.Mesh((2, 0), ()), g.Sharding((4,), (0,)), 0, 2),                # empty mesh dim
+    (g.Mesh((2, 2), (0, 1, 2, 3)), g.Sharding((4, 4), (0, 0)), 0, 3),  # mesh dim used twice
+    (g.Mesh((2, 2), (0, 1, 2, 3)), g.Sharding((4, 4), (0, 2)), 0, 3),  # mesh dim out of range
+    (g.Mesh((2, 2), (0, 1, 2, 3)), g.Sharding((4, 4), (0,)), 0, 3),    # rank mismatch
+    (g.Mesh((2, 2), (0, 1, 2, 3)), g.Sharding((4,), (0,)), 4, 4),      # partition id out of range
+    (g.Mesh((2, 2), (0, 1, 2, 3)), g.Sharding((4,), (0,)), -1, 4),
+])
+def test_bounds_error_codes(mesh, sh, pid, status):
+    with pytest.raises(g.GspmdError) as e:
+        g.shard_bounds(mesh, sh, pid)
+    assert e.value.status == status
+
+
+def test_null_pointers_are_reported():
+    lib = g.load_library()
+    assert lib.gspmd_shard_bounds(None, None, 0, None, None, None) == 1
+
+
+MESH = g.Mesh((4, 8), tuple(range(32)))
+MM = g.DotDims((), (), (1,), (0,))
+
+
+def S(shape, mapping):
+    return g.Sharding(tuple(shape), tuple(mapping))
+
+
+def test_classification_of_the_papers_examples():
+    # Section 3.2: BD,DF->BF with bd on mesh dim 0 and df on mesh dim 1: data + model parallel
+    assert g.classify_dot(MESH, MM, S((64, 32), (0, -1)), S((32, 48), (-1, 1)), S((64, 48), (0, 1))) == (g.AXIS_LHS_FREE, g.AXIS_RHS_FREE)
+    # Section 3.2: EBD,EDF->EBF, experts on mesh dim 0, F on mesh dim 1
+    moe = g.DotDims((0,), (0,), (2,), (1,))
+    assert g.classify_dot(MESH, moe, S((8, 16, 32), (0, -1, -1)), S((8, 32, 48), (0, -1, 1)), S((8, 16, 48), (0, -1, 1))) == (g.AXIS_BATCH, g.AXIS_RHS_FREE)
+    # Table 1, "2D Attempt 1": BSM with M on X, MH on X,Y -> BSH on Y: X carries the contracting dim
+    ffn = g.DotDims((), (), (2,), (0,))
+    assert g.classify_dot(MESH, ffn, S((8, 16, 64), (-1, -1, 0)), S((64, 128), (0, 1)), S((8, 16, 128), (-1, -1, 1))) == (g.AXIS_CONTRACTING, g.AXIS_RHS_FREE)
+    # Table 1, "2D finalized" after the AllGathers: bSM, Mh -> bSh (B on X, H on Y)
+    assert g.classify_dot(MESH, ffn, S((8, 16, 64), (0, -1, -1)), S((64, 128), (-1, 1)), S((8, 16, 128), (0, -1, 1))) == (g.AXIS_LHS_FREE, g.AXIS_RHS_FREE)
+    # nothing split at all
+    assert g.classify_dot(MESH, MM, S((64, 32), (-1, -1)), S((32, 48), (-1, -1)), S((64, 48), (-1, -1))) == (g.AXIS_UNUSED, g.AXIS_UNUSED)
+
+
+@pytest.mark.parametrize("lhs,rhs,out", [
+    (S((64, 32), (0, -1)), S((32, 48), (-1, -1)), S((64, 48), (-1, -1))),   # lhs rows split, out not: AllGather needed
+    (S((64, 32), (-1, 0)), S((32, 48), (-1, -1)), S((64, 48), (-1, -1))),   # contracting dim split on one side only
+    (S((64, 32), (-1, 0)), S((32, 48), (1, -1)), S((64, 48), (-1, -1))),    # contracting dim on different mesh dims
+    (S((64, 32), (0, -1)), S((32, 48), (-1, 1)), S((64, 48), (1, 0))),      # out split the other way round
+    (S((64, 32), (-1, -1)), S((32, 48), (-1, -1)), S((64, 48), (0, -1))),   # out split, operand replicated (DynamicSlice)
+    (S((64, 32), (0, -1)), S((32, 48), (-1, 0)), S((64, 48), (0, -1))),     # one mesh dim on both free dims
+])
+def test_mismatched_shardings_need_reshard(lhs, rhs, out):
+    with pytest.raises(g.GspmdError) as e:
+        g.classify_dot(MESH, MM, lhs, rhs, out)
+    assert e.value.status == 6
+
+
+@pytest.mark.parametrize("dims,lhs,rhs,out", [
+    (g.DotDims((), (), (1,), (0,)), S((64, 32), (-1, -1)), S((31, 48), (-1, -1)), S((64, 48), (-1, -1))),  # K sizes differ
+    (g.DotDims((), (), (2,), (0,)), S((64, 32), (-1, -1)), S((32, 48), (-1, -1)), S((64, 48), (-1, -1))),  # dim out of range
+    (g.DotDims((0,), (0,), (0,), (1,)), S((4, 32), (-1, -1)), S((4, 32), (-1, -1)), S((4,), (-1,))),       # dim used twice
+    (g.DotDims((), (), (1,), (0,)), S((64, 32), (-1, -1)), S((32, 48), (-1, -1)), S((48, 64), (-1, -1))),  # out shape order
+    (g.DotDims((), (), (1,), (0,)), S((64, 32), (-1, -1)), S((32, 48), (-1, -1)), S((64,), (-1,))),        # out rank
+])
+def test_bad_dot_dims(dims, lhs, rhs, out):
+    with pytest.raises(g.GspmdError) as e:
+        g.classify_dot(MESH, dims, lhs, rhs, out)
+    assert e.value.status == 5
+
+
+def test_size_one_mesh_dim_splits_nothing():
+    mesh = g.Mesh((1, 1), (0,))
+    ffn = g.DotDims((), (), (2,), (0,))
+    # config 2: one device's share, expressed on a (1,1) mesh
+    assert g.classify_dot(mesh, ffn, S((8, 16, 64), (0, -1, -1)), S((64, 128), (-1, 1)), S((8, 16, 128), (0, -1, 1))) == (g.AXIS_LHS_FREE, g.AXIS_RHS_FREE)
+
+
+def test_workspace_query():
+    n_local = g.dot_workspace_bytes(MESH, MM, S((6000, 12288), (0, -1)), S((12288, 10000), (-1, 1)), S((6000, 10000), (0, 1)), 3)
+    n_all = g.dot_workspace_bytes(MESH, MM, S((6000, 12288), (0, -1)), S((12288, 10000), (-1, 1)), S((6000, 10000), (0, 1)), -1)
+    assert n_local == 256 and n_all == 32 * 64
+    mesh = g.Mesh((4,), (0, 1, 2, 3))
+    n_k = g.dot_workspace_bytes(mesh, MM, S((4096, 16384), (-1, 0)), S((16384, 8192), (0, -1)), S((4096, 8192), (-1, -1)), -1)
+    assert n_k == 256 + 4 * 4096 * 8192 * 4     # table + four fp32 partials
+
+
+def test_device_calls_validate_before_touching_the_gpu():
+    # arguments that must be refused on the host, before any HIP call (so this runs without a GPU)
+    buf = g.ShardBuf(0, g.BF16, 0)
+    with pytest.raises(g.GspmdError) as e:
+        g.local_dot(MESH, MM, buf, S((64, 32), (0, -1)), buf, S((32, 48), (-1, -1)), buf, S((64, 48), (-1, -1)), 0)
+    assert e.value.status == 6
+    with pytest.raises(g.GspmdError) as e:   # null data pointers
+        g.local_dot(MESH, MM, buf, S((64, 32), (0, -1)), buf, S((32, 48), (-1, 1)), buf, S((64, 48), (0, 1)), 0)
+    assert e.value.status == 1
+    with pytest.raises(g.GspmdError) as e:   # unknown dtype
+        g.local_dot(MESH, MM, g.ShardBuf(256, 5, 0), S((64, 32), (0, -1)), buf, S((32, 48), (-1, 1)), buf, S((64, 48), (0, 1)), 0)
+    assert e.value.status == 7
+    with pytest.raises(g.GspmdError) as e:   # row stride shorter than the shard's last dim
+        g.local_dot(MESH, MM, g.ShardBuf(256, g.BF16, 16), S((64, 32), (0, -1)), g.ShardBuf(256, g.BF16, 0), S((32, 48), (-1, 1)),
+                    g.ShardBuf(256, g.BF16, 0), S((64, 48), (0, 1)), 0)
+    assert e.value.status == 10
+    with pytest.raises(g.GspmdError) as e:   # unsupported layout: lhs contracting dim leading
+        g.local_dot(MESH, g.DotDims((), (), (0,), (0,)), g.ShardBuf(256, g.BF16, 0), S((32, 64), (-1, 0)), g.ShardBuf(256, g.BF16, 0),
+                    S((32, 48), (-1, 1)), g.ShardBuf(256, g.BF16, 0), S((64, 48), (0, 1)), 0)
+    assert e.value.status == 7
+    with pytest.raises(g.GspmdError) as e:
+        g.reduce_partials([], 10, 256, g.F32)
+    assert e.value.status == 10
