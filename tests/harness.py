@@ -138,3 +138,10 @@ class Staged:
             g.shard_assemble(self.mesh, self.out_sh, pid, self.out[pid][0], glob.data_ptr())
         torch.cuda.synchronize()
         return to_f64(glob)
+
+
+def out_tensor(st: "Staged", pid) -> torch.Tensor:
+    """Device view [rows, cols] (static shard shape, row padding cut off) of an out shard."""
+    _, t, ld, shard = st.out[pid]
+    rows = int(np.prod(shard[:-1], dtype=np.int64))
+    return t[:rows * ld].view(rows, ld)[:, :shard[-1]]
