@@ -33,7 +33,10 @@ def parse():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--headline-only", action="store_true", help="skip the other configs and the CPU baseline")
-    ap.add_argument("--cpu-rows", type=int, default=4096, help="rows of the FFN output the CPU oracle is timed on")
+    ap.add_argument("--cpu-rows", type=int, default=16384, help="rows of the FFN output the CPU oracle is timed on")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run only a plain copy of known size (shard_extract of a [16384,8192] bf16 tensor on a 1-partition "
+                         "mesh: 268435456 bytes read, 268435456 written per launch) for scaling HBM byte counters")
     return ap.parse_args()
 
 
@@ -54,6 +57,18 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     stream = torch.cuda.current_stream().cuda_stream
+
+    if args.calibrate_copy:
+        src = torch.randn(16384, 8192, device=dev).to(torch.bfloat16)
+        dst = torch.empty_like(src)
+        mesh, sh = g.Mesh((1,), (0,)), g.Sharding((16384, 8192), (-1, -1))
+        for _ in range(5):
+            g.shard_extract(mesh, sh, 0, src.data_ptr(), g.ShardBuf.of(dst, 0), 0, stream)
+        torch.cuda.synchronize()
+        assert torch.equal(src, dst)
+        print(json.dumps({"calibrate_copy": "shard_copy_kernel", "launches": 5, "bytes_read_per_launch": src.numel() * 2,
+                          "bytes_written_per_launch": src.numel() * 2}), flush=True)
+        return
 
     def dev_tensor(arr, dtype):
         if dtype == "bf16":
