@@ -1,124 +1,131 @@
 #!/usr/bin/env python3
 """Writes mainloop_asm.h: the inline-assembly text of the MFMA kernel's K loop (gfx950).
 
-Run `python gen_mainloop.py > mainloop_asm.h` after changing the schedule; the generated
-header is committed, the build does not run this script.
+Run `python gen_mainloop.py > mainloop_asm.h` after changing the schedule; the generated header is committed,
+the build does not run this script.
 
-The loop is a ping-pong between the two wave groups of a workgroup (waves 0-3 and 4-7; the
-hardware places wave w and wave w+4 on the same SIMD).  Per K step of 64 a group alternates
-between a memory phase (32 LDS fragment reads for the whole step) and an MFMA phase (32
-v_mfma_f32_32x32x16_bf16 with no waits); the groups are offset by one phase, with an s_barrier
-between phases, so each SIMD's matrix pipe always has one wave issuing MFMAs while the other
-wave fetches.  Global->LDS tile loads (global_load_lds_dwordx4, 8 per wave per K step) go
-into the stage both groups have finished reading: group 0 issues them in its memory phase,
-group 1 between the MFMAs of its MFMA phase.
+Shape of the loop.  K advances in steps of 64 = two LDS tiles of 32.  LDS has five 32 KiB stages (tile t lives in
+stage t % 5: A part [256 m][32 k], B part [32 k][256 n]).  The workgroup's two wave groups (waves 0-3 and 4-7; wave
+w and w+4 share a SIMD) alternate, one phase apart and separated by s_barrier, between
+  * a read phase: all fragments of one K step, 32 LDS reads (16 ds_read_b128 for A, 16 ds_read_b64_tr_b16 for B)
+    into 96 VGPRs, and
+  * an MFMA phase: 64 v_mfma_f32_16x16x32_bf16 with no waits,
+so that each SIMD's matrix pipe always has exactly one wave issuing MFMAs (two waves issuing at once share the pipe
+badly: measured 64 % pipe efficiency with one wave starved).  16x16x32 is used rather than 32x32x16 because it moves
+half the accumulator registers per flop and the chip is power-limited: a pure MFMA loop on N(0,1) data sustains
+1996 TFLOP/s with 16x16x32 and 1700 with 32x32x16 (both reach 2480 on all-zero data).
+Global->LDS tile loads (global_load_lds_dwordx4, 1 KiB per wave-instruction) are issued only from MFMA phases, one
+after every 8th MFMA and staggered by wave, so the CU's texture-address unit (about one such load per 16 cycles) sees
+an even stream and never stalls an MFMA wave; a whole tile is loaded by the four waves of ONE group: group 0 loads
+tile 2u+4 during the MFMA phase of step u, group 1 tile 2u+5.  With five stages every load has at least one full
+phase (>= 1024 cycles) plus the slack of a read phase to land; s_waitcnt vmcnt sits right before the barrier that
+publishes the tile.
 
-Register plan per wave: v[0:127] accumulators acc[mi][ni] = v[16*(2*mi+ni) ..+15];
-v[128:191] A fragments fa[kk][mi] = v[128+4*(4*kk+mi) ..+3]; v[192:223] B fragments
-fb[kk][ni] = v[192+4*(2*kk+ni) ..+3]; v[224:227] A read addresses per kk.
-SGPRs: s[40:41] / s[42:43] pointers to the next A / B tile to load, s44 this wave's LDS write
-base in the stage being filled, s45 K steps left, s46 pointer advances left (the pointer stops
-at the last full tile: loads issued past it re-read that tile into a stage nobody reads any
-more), s47 B pointer step in bytes, s48-s50 temporaries.
+Register plan per wave: v[0:127] accumulators acc(bm, bn) = v[4*(4*bm+bn) ..+3] (bm = 16-row block 0..7 of the
+wave's 128 rows, bn = 16-column block 0..3 of its 64 columns); fragments of tile q (0/1) of the K step:
+A fa_q[bm] = v[128+48q+4bm ..+3], B fb_q[bn] = v[160+48q+4bn ..+3]; v224 A read address, v225..v228 B read
+addresses (per bn) in the stage being read.
+SGPRs: s[40:41]/s[42:43] pointers to the next A/B tile this group loads, s44 this wave's LDS write base (stage 0),
+s45 K steps left, s46 pointer advances left (the pointers stop at the last full tile: loads issued past it re-read
+that tile into a stage nobody reads any more), s47 B pointer step in bytes (two tiles), s52 write-stage offset,
+s53 read-stage offset, s48-s51 temporaries.
 """
 import sys
 
-STAGE_A = 0x8000      # bytes of the A tile inside a stage; a stage is 0x10000 bytes
+STAGE = 0x8000
+STAGE_A = 0x4000
+NSTAGE = 5
+LDS = STAGE * NSTAGE
 
 
-def acc(mi, ni):
-    b = 16 * (2 * mi + ni)
-    return f"v[{b}:{b + 15}]"
-
-
-def fa(kk, mi):
-    b = 128 + 4 * (4 * kk + mi)
+def acc(bm, bn):
+    b = 4 * (4 * bm + bn)
     return f"v[{b}:{b + 3}]"
 
 
-def fb(kk, ni, half=None):
-    b = 192 + 4 * (2 * kk + ni)
+def fa(q, bm):
+    b = 128 + 48 * q + 4 * bm
+    return f"v[{b}:{b + 3}]"
+
+
+def fb(q, bn, half=None):
+    b = 160 + 48 * q + 4 * bn
     if half is None:
         return f"v[{b}:{b + 3}]"
     return f"v[{b + 2 * half}:{b + 2 * half + 1}]"
 
 
-def setup():
-    # the A read address of k-substep kk differs from that of substep 0 by kk*32 XORed in
-    return ["v_mov_b32 v224, %[ard]",
-            "v_xor_b32 v225, 32, %[ard]",
-            "v_xor_b32 v226, 64, %[ard]",
-            "v_xor_b32 v227, 0x60, %[ard]"]
+def read_addrs():
+    return ["v_add_u32 v224, s53, %[ard]",
+            "v_add_u32 v225, s53, %[brd]",
+            "v_xor_b32 v226, 32, v225",
+            "v_xor_b32 v227, 64, v225",
+            "v_xor_b32 v228, 0x60, v225"]
 
 
-def ds_reads():
+def ds_reads(q):
     out = []
-    for kk in range(4):
-        for mi in range(4):
-            out.append(f"ds_read_b128 {fa(kk, mi)}, v{224 + kk} offset:{mi * 4096}")
-        for ni in range(2):
-            for rd in range(2):
-                out.append(f"ds_read_b64_tr_b16 {fb(kk, ni, rd)}, %[brd{ni}] offset:{kk * 8192 + rd * 2048}")
+    for bm in range(8):
+        out.append(f"ds_read_b128 {fa(q, bm)}, v224 offset:{bm * 1024}")
+    for bn in range(4):
+        for rd in range(2):
+            out.append(f"ds_read_b64_tr_b16 {fb(q, bn, rd)}, v{225 + bn} offset:{rd * 2048}")
     return out
 
 
-def toggles():
-    """Point the fragment reads at the other stage."""
-    out = [f"v_xor_b32 v{224 + kk}, 0x10000, v{224 + kk}" for kk in range(4)]
-    out += ["v_xor_b32 %[brd0], 0x10000, %[brd0]", "v_xor_b32 %[brd1], 0x10000, %[brd1]"]
-    return out
+def step_stage(reg, n):
+    return [f"s_add_u32 {reg}, {reg}, {STAGE * n}", f"s_sub_u32 s48, {reg}, {LDS}", f"s_cmp_ge_u32 {reg}, {LDS}", f"s_cselect_b32 {reg}, s48, {reg}"]
+
+
+def mem_phase():
+    return read_addrs() + ds_reads(0) + step_stage("s53", 1) + read_addrs() + ds_reads(1) + step_stage("s53", 1)
 
 
 def load(j):
-    """Wave-instruction j of a tile: 1 KiB, 16 bytes per lane, straight into LDS at m0 + lane*16."""
     if j < 4:
-        return [f"s_add_u32 m0, s44, {j * 1024}", "s_nop 0", f"global_load_lds_dwordx4 %[ao{j}], s[40:41]"]
-    return [f"s_add_u32 m0, s44, {STAGE_A + (j - 4) * 1024}", "s_nop 0",
-            f"global_load_lds_dwordx4 %[bo{j - 4}], s[42:43]"]
+        return [f"s_add_u32 m0, s49, {j * 1024}", "s_nop 0", f"global_load_lds_dwordx4 %[ao{j}], s[40:41]"]
+    return [f"s_add_u32 m0, s49, {STAGE_A + (j - 4) * 1024}", "s_nop 0", f"global_load_lds_dwordx4 %[bo{j - 4}], s[42:43]"]
 
 
 def advance():
+    """Next tile of this group (two tiles on), pointers frozen at the last full tile; next write stage."""
     return ["s_cmp_lg_u32 s46, 0",
-            "s_cselect_b32 s48, 128, 0",
-            "s_cselect_b32 s49, s47, 0",
-            "s_cselect_b32 s50, 1, 0",
-            "s_add_u32 s40, s40, s48", "s_addc_u32 s41, s41, 0",
-            "s_add_u32 s42, s42, s49", "s_addc_u32 s43, s43, 0",
-            "s_sub_u32 s46, s46, s50",
-            "s_xor_b32 s44, s44, 0x10000"]
+            "s_cselect_b32 s50, 128, 0",
+            "s_cselect_b32 s51, s47, 0",
+            "s_cselect_b32 s48, 1, 0",
+            "s_sub_u32 s46, s46, s48",
+            "s_add_u32 s40, s40, s50", "s_addc_u32 s41, s41, 0",
+            "s_add_u32 s42, s42, s51", "s_addc_u32 s43, s43, 0"] + step_stage("s52", 2)
 
 
-def mfmas(loads_after=None):
-    out, i = [], 0
-    for kk in range(4):
-        for mi in range(4):
-            for ni in range(2):
-                # rhs fragment as first operand: the accumulator gets 4 consecutive n per lane
-                out.append(f"v_mfma_f32_32x32x16_bf16 {acc(mi, ni)}, {fb(kk, ni)}, {fa(kk, mi)}, {acc(mi, ni)}")
-                if loads_after and i in loads_after:
-                    out += load(loads_after[i])
+def mfma_phase(w):
+    load_pos = {8 * j + 2 * w: j for j in range(8)}
+    out = ["s_add_u32 s49, s44, s52"]
+    i = 0
+    for q in range(2):
+        for bm in range(8):
+            for bn in range(4):
+                out.append(f"v_mfma_f32_16x16x32_bf16 {acc(bm, bn)}, {fb(q, bn)}, {fa(q, bm)}, {acc(bm, bn)}")
+                if i in load_pos:
+                    out += load(load_pos[i])
                 i += 1
+    out += advance()
     return out
 
 
-def group0():
-    s = setup() + ["L0_top_%=:"] + ds_reads()
-    for j in range(8):
-        s += load(j)
-    s += advance() + toggles()
-    s += ["s_waitcnt lgkmcnt(0)", "s_barrier"]
-    s += mfmas()
-    s += ["s_waitcnt vmcnt(0)", "s_barrier",
-          "s_sub_u32 s45, s45, 1", "s_cmp_lg_u32 s45, 0", "s_cbranch_scc1 L0_top_%=",
-          "s_nop 15", "s_nop 15"]
+def group0(w):
+    """Waves 0-3: read phase of K step u, barrier, MFMA phase of u (loading tile 2u+4), barrier."""
+    s = ["L0_top_%=:"] + mem_phase() + ["s_waitcnt lgkmcnt(0)", "s_barrier"]
+    s += mfma_phase(w)
+    s += ["s_waitcnt vmcnt(8)", "s_barrier",
+          "s_sub_u32 s45, s45, 1", "s_cmp_lg_u32 s45, 0", "s_cbranch_scc1 L0_top_%=", "s_nop 15", "s_nop 15"]
     return s
 
 
-def group1():
-    s = setup() + ["s_barrier", "L1_top_%=:"] + ds_reads() + toggles()
-    s += ["s_waitcnt vmcnt(0) lgkmcnt(0)", "s_barrier"]
-    s += mfmas({1 + 4 * j: j for j in range(8)})
-    s += advance()
+def group1(w):
+    """Waves 4-7: one phase behind group 0 (extra barrier first); loads tile 2u+5 in its MFMA phase."""
+    s = ["s_barrier", "L1_top_%=:"] + mem_phase() + ["s_waitcnt vmcnt(0) lgkmcnt(0)", "s_barrier"]
+    s += mfma_phase(w)
     s += ["s_sub_u32 s45, s45, 1", "s_cmp_lg_u32 s45, 0", "s_cbranch_scc0 L1_end_%=",
           "s_barrier", "s_branch L1_top_%=", "L1_end_%=:", "s_nop 15", "s_nop 15"]
     return s
@@ -129,10 +136,12 @@ def macro(name, lines):
 
 
 def main():
-    clob = ", ".join(f'"v{i}"' for i in range(128, 228))
-    out = ["// Generated by gen_mainloop.py -- do not edit by hand.", "#pragma once",
-           macro("GSPMD_MAINLOOP_G0", group0()), macro("GSPMD_MAINLOOP_G1", group1()),
-           f'#define GSPMD_MAINLOOP_CLOBBERS {clob}, "s48", "s49", "s50", "m0", "scc", "vcc", "memory"']
+    clob = ", ".join(f'"v{i}"' for i in range(128, 229))
+    out = ["// Generated by gen_mainloop.py -- do not edit by hand.", "#pragma once"]
+    for w in range(4):
+        out.append(macro(f"GSPMD_MAINLOOP_G0_W{w}", group0(w)))
+        out.append(macro(f"GSPMD_MAINLOOP_G1_W{w}", group1(w)))
+    out.append(f'#define GSPMD_MAINLOOP_CLOBBERS {clob}, "s48", "s49", "s50", "s51", "m0", "scc", "vcc", "memory"')
     sys.stdout.write("\n".join(out) + "\n")
 
 
