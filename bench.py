@@ -24,6 +24,9 @@ import numpy as np
 
 PEAK_BF16_TFLOPS = 2516.6   # 256 CU x 4096 flop/clk/CU x 2.4 GHz (dense bf16 MFMA)
 PEAK_HBM_GBS = 8000.0
+# L2 <-> fabric bytes of one dot_mfma_kernel launch on the FFN share, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled
+# by a copy kernel of known size (profiles/dot_mfma_kernel_ffn_share.md): 3.228e9 fetched + 0.272e9 written
+FFN_TRAFFIC_BYTES = 3.228e9 + 0.272e9
 METRIC = "per-shard einsum bf16 TFLOP/s and % of MI355X MFMA peak (1 GPU)"
 
 
@@ -153,7 +156,8 @@ def main():
                    "einsum": w.einsum, "useful_flops": flops, "entry_point": "gspmd_grouped_dot"},
         "pct_of_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
         "roofline": {"bound": "mfma", "achieved": round(kern_tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(kern_tflops / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "frac": round(kern_tflops / PEAK_BF16_TFLOPS, 4), "traffic": FFN_TRAFFIC_BYTES,
+                     "algorithmic_bytes": 16384 * 8192 * 2 + 8192 * 8192 * 2 + 16384 * 8192 * 2,
                      "kernel": "dot_mfma_kernel", "kernel_ms": round(ev_ms, 4)},
     }
 
