@@ -118,6 +118,28 @@ int32_t gspmd_classify_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
                            const gspmd_sharding* lhs_sh, const gspmd_sharding* rhs_sh,
                            const gspmd_sharding* out_sh, int32_t* axis_class);
 
+/* One strided GEMM of the list a partition's local Dot is lowered to:
+ *   C[m, n] = sum_k A[m, k] * B[k, n]   for m < m_valid, n < n_valid, k < k_valid,   C = 0 on the rest of
+ *   [m_static, n_static];  A[m,k] at lhs element a_offset + m*lda + k, B[k,n] at rhs element b_offset + k*ldb + n,
+ *   C[m,n] at out element c_offset + m*ldc + n (offsets in elements from the shard buffers' data pointers). */
+typedef struct {
+  int64_t a_offset, b_offset, c_offset;
+  int64_t lda, ldb, ldc;
+  int32_t m_valid, n_valid, k_valid;
+  int32_t m_static, n_static;
+  int32_t reserved;
+} gspmd_gemm_desc;
+
+/* How gspmd_local_dot lowers partition `partition_id`'s Dot (shard bounds -> flattened batch / free / contracting
+ * extents -> one GEMM per batch entry and per index of a free dimension that padding keeps from flattening), without
+ * touching the GPU.  *_row_stride as in gspmd_shard_buf (0 = dense).  Writes min(count, capacity) descriptors to
+ * `descs` (may be NULL when capacity is 0) and the total to `count`.  Pure host work; for inspection and tests. */
+int32_t gspmd_plan_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
+                       const gspmd_sharding* lhs_sh, const gspmd_sharding* rhs_sh, const gspmd_sharding* out_sh,
+                       int64_t lhs_row_stride, int64_t rhs_row_stride, int64_t out_row_stride,
+                       int64_t partition_id, const int64_t* lhs_fill,
+                       gspmd_gemm_desc* descs, int64_t capacity, int64_t* count);
+
 /* Bytes of device workspace gspmd_local_dot (partition_id >= 0) or gspmd_grouped_dot
  * (partition_id = -1: all partitions) needs for these arguments.  `has_fill` says whether a
  * fill-count array will be passed.  Pure host work. */

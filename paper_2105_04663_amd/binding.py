@@ -12,7 +12,7 @@ AXIS_UNUSED, AXIS_BATCH, AXIS_LHS_FREE, AXIS_RHS_FREE, AXIS_CONTRACTING = range(
 EXPORTED_SYMBOLS = (
     "gspmd_status_string", "gspmd_shard_bounds", "gspmd_classify_dot", "gspmd_dot_workspace_bytes",
     "gspmd_local_dot", "gspmd_grouped_dot", "gspmd_reduce_partials", "gspmd_shard_extract",
-    "gspmd_shard_assemble",
+    "gspmd_shard_assemble", "gspmd_plan_dot",
 )
 
 
@@ -37,6 +37,13 @@ class _CDotDims(C.Structure):
 
 class _CShardBuf(C.Structure):
     _fields_ = [("data", C.c_void_p), ("dtype", C.c_int32), ("row_stride", C.c_int64)]
+
+
+class _CGemmDesc(C.Structure):
+    _fields_ = [("a_offset", C.c_int64), ("b_offset", C.c_int64), ("c_offset", C.c_int64),
+                ("lda", C.c_int64), ("ldb", C.c_int64), ("ldc", C.c_int64),
+                ("m_valid", C.c_int32), ("n_valid", C.c_int32), ("k_valid", C.c_int32),
+                ("m_static", C.c_int32), ("n_static", C.c_int32), ("reserved", C.c_int32)]
 
 
 _LIB = None
@@ -67,6 +74,8 @@ def load_library():
     lib.gspmd_reduce_partials.argtypes = [C.POINTER(C.c_void_p), C.c_int32, C.c_int64, C.c_void_p, C.c_int32, C.c_void_p]
     lib.gspmd_shard_extract.argtypes = [pm, ps, C.c_int64, C.c_void_p, pb, C.c_uint32, C.c_void_p]
     lib.gspmd_shard_assemble.argtypes = [pm, ps, C.c_int64, pb, C.c_void_p, C.c_void_p]
+    lib.gspmd_plan_dot.argtypes = [pm, pd, ps, ps, ps, C.c_int64, C.c_int64, C.c_int64, C.c_int64, pi64,
+                                   C.POINTER(_CGemmDesc), C.c_int64, pi64]
     for name in EXPORTED_SYMBOLS[1:]:
         getattr(lib, name).restype = C.c_int32
     _LIB = lib
@@ -188,6 +197,20 @@ def dot_workspace_bytes(mesh: Mesh, dims: DotDims, lhs_sh: Sharding, rhs_sh: Sha
     _check(load_library().gspmd_dot_workspace_bytes(C.byref(m), C.byref(d), C.byref(a), C.byref(b), C.byref(o),
                                                     int(partition_id), int(has_fill), C.byref(n)), "gspmd_dot_workspace_bytes")
     return int(n.value)
+
+
+def plan_dot(mesh: Mesh, dims: DotDims, lhs_sh: Sharding, rhs_sh: Sharding, out_sh: Sharding, partition_id: int,
+             lhs_row_stride: int = 0, rhs_row_stride: int = 0, out_row_stride: int = 0, lhs_fill=None) -> List[dict]:
+    """The strided GEMMs partition `partition_id`'s local Dot is lowered to (host only)."""
+    m, d, a, b, o = mesh._c(), dims._c(), lhs_sh._c(), rhs_sh._c(), out_sh._c()
+    n = C.c_int64(0)
+    lib = load_library()
+    args = (C.byref(m), C.byref(d), C.byref(a), C.byref(b), C.byref(o), int(lhs_row_stride), int(rhs_row_stride),
+            int(out_row_stride), int(partition_id), _fill(lhs_fill))
+    _check(lib.gspmd_plan_dot(*args, None, 0, C.byref(n)), "gspmd_plan_dot")
+    arr = (_CGemmDesc * max(1, n.value))()
+    _check(lib.gspmd_plan_dot(*args, arr, n.value, C.byref(n)), "gspmd_plan_dot")
+    return [{f: getattr(arr[i], f) for f, _ in _CGemmDesc._fields_ if f != "reserved"} for i in range(n.value)]
 
 
 def _fill(fill):

@@ -45,6 +45,7 @@ bool mfma_eligible(const std::vector<Problem>& ps, int32_t in_dtype) {
     if (p.Kv == 0) continue;
     if ((reinterpret_cast<uintptr_t>(p.A) | reinterpret_cast<uintptr_t>(p.B)) & 15) return false;
     if ((p.lda & 7) || (p.ldb & 7)) return false;
+    if (p.lda > (1 << 22) || p.ldb > (1 << 24)) return false;   // 32-bit byte offsets inside a tile
   }
   return true;
 }
@@ -152,6 +153,40 @@ int32_t gspmd_classify_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
   const int32_t st = analyse_dot(mesh, dims, lhs_sh, rhs_sh, out_sh, &r, cls);
   if (st != GSPMD_OK) return st;
   for (int a = 0; a < mesh->rank; ++a) axis_class[a] = cls[a];
+  return GSPMD_OK;
+}
+
+int32_t gspmd_plan_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
+                       const gspmd_sharding* lhs_sh, const gspmd_sharding* rhs_sh, const gspmd_sharding* out_sh,
+                       int64_t lhs_row_stride, int64_t rhs_row_stride, int64_t out_row_stride,
+                       int64_t pid, const int64_t* lhs_fill,
+                       gspmd_gemm_desc* descs, int64_t capacity, int64_t* count) {
+  if (!count || (capacity > 0 && !descs)) return GSPMD_ERR_NULL;
+  if (capacity < 0 || lhs_row_stride < 0 || rhs_row_stride < 0 || out_row_stride < 0) return GSPMD_ERR_BAD_BUFFER;
+  DotRoles r;
+  int32_t cls[kMaxRank];
+  int32_t st = analyse_dot(mesh, dims, lhs_sh, rhs_sh, out_sh, &r, cls);
+  if (st != GSPMD_OK) return st;
+  // plan against made-up base addresses far apart, with 1-byte elements, so that pointer differences are element offsets
+  const uintptr_t base_a = uintptr_t(1) << 44, base_b = uintptr_t(2) << 44, base_c = uintptr_t(3) << 44;
+  gspmd_shard_buf la{reinterpret_cast<void*>(base_a), GSPMD_F32, lhs_row_stride};
+  gspmd_shard_buf rb{reinterpret_cast<void*>(base_b), GSPMD_F32, rhs_row_stride};
+  gspmd_shard_buf oc{reinterpret_cast<void*>(base_c), GSPMD_F32, out_row_stride};
+  std::vector<Problem> ps;
+  int64_t elems = 0;
+  if ((st = plan_partition(mesh, r, &la, lhs_sh, &rb, rhs_sh, &oc, out_sh, pid, lhs_fill, nullptr, &ps, &elems)) != GSPMD_OK) return st;
+  *count = static_cast<int64_t>(ps.size());
+  for (int64_t i = 0; i < std::min<int64_t>(capacity, *count); ++i) {
+    const Problem& p = ps[static_cast<size_t>(i)];
+    gspmd_gemm_desc& d = descs[i];
+    d.a_offset = static_cast<int64_t>(reinterpret_cast<uintptr_t>(p.A) - base_a) / 4;
+    d.b_offset = static_cast<int64_t>(reinterpret_cast<uintptr_t>(p.B) - base_b) / 4;
+    d.c_offset = static_cast<int64_t>(reinterpret_cast<uintptr_t>(p.C) - base_c) / 4;
+    d.lda = p.lda; d.ldb = p.ldb; d.ldc = p.ldc;
+    d.m_valid = p.Mv; d.n_valid = p.Nv; d.k_valid = p.Kv;
+    d.m_static = p.Ms; d.n_static = p.Ns;
+    d.reserved = 0;
+  }
   return GSPMD_OK;
 }
 

@@ -1,0 +1,137 @@
+"""CPU test of the host lowering (shard bounds -> flattened GEMM problems): the descriptors returned by
+gspmd_plan_dot are executed with numpy on poisoned, padded shard buffers and the result is compared with the
+oracle's expected out shard.  No GPU: this pins row a1-a3/a6 host logic independently of the kernels."""
+import numpy as np
+import pytest
+from hypothesis import HealthCheck, given, settings, strategies as st
+
+import paper_2105_04663_amd as g
+from oracle import bounds as ob
+from oracle import dot as od
+
+
+def shard_strides(shard, row_stride):
+    """Element strides of a shard buffer as the header defines them."""
+    r = len(shard)
+    s = [0] * r
+    s[-1] = 1
+    if r >= 2:
+        s[-2] = row_stride if row_stride else shard[-1]
+        for i in range(r - 3, -1, -1):
+            s[i] = s[i + 1] * shard[i + 1]
+    return s
+
+
+def make_shard(glob, mesh_shape, ids, mapping, pid, row_stride, poison=np.nan):
+    off, valid, shard = ob.shard_bounds(mesh_shape, ids, glob.shape, mapping, pid)
+    strides = shard_strides(shard, row_stride)
+    size = 1 + sum((d - 1) * s for d, s in zip(shard, strides)) if all(d > 0 for d in shard) else 1
+    buf = np.full(size + 3, poison, dtype=np.float64)
+    view = np.lib.stride_tricks.as_strided(buf, shape=shard, strides=[8 * s for s in strides])
+    sl = tuple(slice(0, v) for v in valid)
+    view[sl] = glob[tuple(slice(o, o + v) for o, v in zip(off, valid))]
+    return buf, view, shard, valid
+
+
+def run_plan(descs, a, b, c):
+    for d in descs:
+        M, N, K = d["m_valid"], d["n_valid"], d["k_valid"]
+        A = np.lib.stride_tricks.as_strided(a[d["a_offset"]:], shape=(M, K), strides=(8 * d["lda"], 8)) if M and K else np.zeros((M, K))
+        B = np.lib.stride_tricks.as_strided(b[d["b_offset"]:], shape=(K, N), strides=(8 * d["ldb"], 8)) if N and K else np.zeros((K, N))
+        C = np.lib.stride_tricks.as_strided(c[d["c_offset"]:], shape=(d["m_static"], d["n_static"]), strides=(8 * d["ldc"], 8))
+        C[:, :] = 0.0
+        if M and N and K:
+            assert np.isfinite(A).all() and np.isfinite(B).all(), "a descriptor reaches into padding"
+            C[:M, :N] = A @ B
+
+
+@st.composite
+def sharded_dot(draw):
+    nb, nlf, nc, nrf = draw(st.integers(0, 2)), draw(st.integers(1, 2)), draw(st.integers(1, 2)), draw(st.integers(1, 2))
+    size = lambda: draw(st.integers(1, 7))
+    bsz, lfsz, csz, rfsz = [size() for _ in range(nb)], [size() for _ in range(nlf)], [size() for _ in range(nc)], [size() for _ in range(nrf)]
+    lhs_shape, rhs_shape, out_shape = bsz + lfsz + csz, bsz + csz + rfsz, bsz + lfsz + rfsz
+    mrank = draw(st.integers(1, 3))
+    mshape = [draw(st.integers(1, 3)) for _ in range(mrank)]
+    P = int(np.prod(mshape))
+    ids = draw(st.permutations(list(range(P))))
+    lmap, rmap, omap = [-1] * len(lhs_shape), [-1] * len(rhs_shape), [-1] * len(out_shape)
+    # each mesh dim carries one of the communication-free patterns on a dim not yet split
+    free = {"b": list(range(nb)), "l": list(range(nlf)), "c": list(range(nc)), "r": list(range(nrf))}
+    for axis in range(mrank):
+        kinds = [k for k in "blcr" if free[k]] + ["u"]
+        kind = draw(st.sampled_from(kinds))
+        if kind == "u":
+            continue
+        i = free[kind].pop(draw(st.integers(0, len(free[kind]) - 1)))
+        if kind == "b":
+            lmap[i] = rmap[i] = omap[i] = axis
+        elif kind == "l":
+            lmap[nb + i] = omap[nb + i] = axis
+        elif kind == "r":
+            rmap[nb + nc + i] = omap[nb + nlf + i] = axis
+        else:
+            lmap[nb + nlf + i] = rmap[nb + i] = axis
+    strides = [draw(st.sampled_from([0, 1, 3])) for _ in range(3)]     # extra row padding per tensor
+    return dict(lhs_shape=tuple(lhs_shape), rhs_shape=tuple(rhs_shape), out_shape=tuple(out_shape), nb=nb, nlf=nlf, nc=nc, nrf=nrf,
+                mshape=tuple(mshape), ids=tuple(ids), lmap=tuple(lmap), rmap=tuple(rmap), omap=tuple(omap), pad=strides,
+                seed=draw(st.integers(0, 1 << 30)))
+
+
+@settings(max_examples=250, deadline=None, suppress_health_check=[HealthCheck.too_slow])
+@given(sharded_dot())
+def test_lowered_problems_reproduce_the_oracle(c):
+    rng = np.random.default_rng(c["seed"])
+    lhs = rng.integers(-4, 5, size=c["lhs_shape"]).astype(np.float64)
+    rhs = rng.integers(-4, 5, size=c["rhs_shape"]).astype(np.float64)
+    nb, nlf, nc = c["nb"], c["nlf"], c["nc"]
+    lb, rb = tuple(range(nb)), tuple(range(nb))
+    lc, rc = tuple(range(nb + nlf, nb + nlf + nc)), tuple(range(nb, nb + nc))
+    dims = (lb, rb, lc, rc)
+    mesh, gd = g.Mesh(c["mshape"], c["ids"]), g.DotDims(lb, rb, lc, rc)
+    lsh, rsh, osh = g.Sharding(c["lhs_shape"], c["lmap"]), g.Sharding(c["rhs_shape"], c["rmap"]), g.Sharding(c["out_shape"], c["omap"])
+    contracting = g.AXIS_CONTRACTING in g.classify_dot(mesh, gd, lsh, rsh, osh)
+    out_global = od.dot_general(lhs, rhs, *dims)
+    for pid in range(len(c["ids"])):
+        def rs(shape_map, glob, extra):
+            _, _, shard = ob.shard_bounds(c["mshape"], c["ids"], glob, shape_map, pid)
+            return shard[-1] + extra if (extra and len(shard) >= 2) else 0
+        lrs, rrs, ors = rs(c["lmap"], c["lhs_shape"], c["pad"][0]), rs(c["rmap"], c["rhs_shape"], c["pad"][1]), rs(c["omap"], c["out_shape"], c["pad"][2])
+        try:
+            descs = g.plan_dot(mesh, gd, lsh, rsh, osh, pid, lrs, rrs, ors)
+        except g.GspmdError as e:
+            # the only refusal allowed here: several contracting dims that padding or row padding keeps from flattening
+            assert e.status == 7 and nc > 1
+            continue
+        a, _, _, _ = make_shard(lhs, c["mshape"], c["ids"], c["lmap"], pid, lrs)
+        b, _, _, _ = make_shard(rhs, c["mshape"], c["ids"], c["rmap"], pid, rrs)
+        cbuf, cview, cshard, cvalid = make_shard(np.full(c["out_shape"], 7.0), c["mshape"], c["ids"], c["omap"], pid, ors, poison=7.0)
+        run_plan(descs, a, b, cbuf)
+        if contracting:
+            want_full = od.expected_partial(lhs, rhs, dims, c["mshape"], c["ids"], c["lmap"], c["rmap"], pid)
+        else:
+            want_full = out_global
+        want = od.expected_out_shard(want_full, c["mshape"], c["ids"], c["omap"], pid)
+        assert cview.shape == want.shape
+        assert np.array_equal(cview, want), (pid, descs)
+
+
+def test_config_lowerings():
+    import workloads as wl
+    # config 2: one problem, B and S flattened into M
+    w = wl.ffn()
+    d = g.plan_dot(g.Mesh(w.mesh_shape, w.device_ids), g.DotDims((), (), (2,), (0,)), g.Sharding(w.lhs_shape, w.lhs_map),
+                   g.Sharding(w.rhs_shape, w.rhs_map), g.Sharding(w.out_shape, w.out_map), 0)
+    assert len(d) == 1 and (d[0]["m_valid"], d[0]["n_valid"], d[0]["k_valid"]) == (16384, 8192, 8192)
+    # config 4: one problem per expert, rows clamped to the fill count
+    w = wl.moe()
+    fill = w.draw_fill()
+    d = g.plan_dot(g.Mesh(w.mesh_shape, w.device_ids), g.DotDims((0,), (0,), (2,), (1,)), g.Sharding(w.lhs_shape, w.lhs_map),
+                   g.Sharding(w.rhs_shape, w.rhs_map), g.Sharding(w.out_shape, w.out_map), 0, lhs_fill=fill)
+    assert [x["m_valid"] for x in d] == [int(f) for f in fill] and all(x["m_static"] == 1024 for x in d)
+    assert [x["b_offset"] for x in d] == [e * 8192 * 32768 for e in range(4)]
+    # config 5, partition 13 of the 4 x 8 mesh with rows padded to 8 elements
+    w = wl.mesh2d()
+    d = g.plan_dot(g.Mesh(w.mesh_shape, w.device_ids), g.DotDims((), (), (1,), (0,)), g.Sharding(w.lhs_shape, w.lhs_map),
+                   g.Sharding(w.rhs_shape, w.rhs_map), g.Sharding(w.out_shape, w.out_map), 13, 0, 1256, 1256)
+    assert len(d) == 1 and (d[0]["m_valid"], d[0]["n_valid"], d[0]["k_valid"], d[0]["ldb"], d[0]["ldc"]) == (1500, 1250, 12288, 1256, 1256)
