@@ -132,7 +132,7 @@ typedef struct {
 
 /* How gspmd_local_dot lowers partition `partition_id`'s Dot (shard bounds -> flattened batch / free / contracting
  * extents -> one GEMM per batch entry and per index of a free dimension that padding keeps from flattening), without
- * touching the GPU.  *_row_stride as in gspmd_shard_buf (0 = dense).  Writes min(count, capacity) descriptors to
+ * touching the GPU.  *_row_stride as in gspmd_shard_buf: 0 = dense.  Writes min(count, capacity) descriptors to
  * `descs` (may be NULL when capacity is 0) and the total to `count`.  Pure host work; for inspection and tests. */
 int32_t gspmd_plan_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
                        const gspmd_sharding* lhs_sh, const gspmd_sharding* rhs_sh, const gspmd_sharding* out_sh,
