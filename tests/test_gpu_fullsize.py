@@ -97,3 +97,33 @@ def test_config5_nested_mesh_full_size(make):
     ref = od.dot_general(wl.bf16_bits_to_f64(lhs[rows]), wl.bf16_bits_to_f64(rhs), (), (), (1,), (0,))
     got = to_f64(glob[torch.from_numpy(rows).cuda()].contiguous())
     check(got, ref, w.name)
+
+
+def test_second_ffn_einsum_full_size():
+    # BSH,HM->BSM, H = 4 x 8192 split over 4 partitions: fp32 partials summed on the GPU, bf16 result
+    w = wl.ffn_second()
+    lhs, rhs = w.draw_lhs(), w.draw_rhs()
+    st = Staged(w, lhs, rhs, row_align=8)
+    st.run_grouped()
+    torch.cuda.synchronize()
+    s_idx = sample_rows(2048, [256, 1024], seed=7, extra=4)
+    ref = od.dot_general(wl.bf16_bits_to_f64(lhs[:2][:, s_idx, :]), wl.bf16_bits_to_f64(rhs), (), (), (2,), (0,))
+    out = out_tensor(st, 0).view(8, 2048, 8192)
+    got = to_f64(out[:2][:, torch.from_numpy(s_idx).cuda(), :].contiguous())
+    check(got, ref, "BSH,HM->BSM")
+
+
+def test_second_moe_einsum_full_size():
+    w = wl.moe_second()
+    fill = w.draw_fill()
+    lhs, rhs = w.draw_lhs(), w.draw_rhs()
+    st = Staged(w, lhs, rhs, row_align=8)
+    st.run_grouped(fill=fill)
+    torch.cuda.synchronize()
+    out = out_tensor(st, 0).view(4, 1024, 8192)
+    for e in range(4):
+        f = int(fill[e])
+        assert not bool(out[e, f:].any())
+        rows = sample_rows(f, [256, 512], seed=80 + e, extra=4)
+        ref = od.dot_general(wl.bf16_bits_to_f64(lhs[e, rows]), wl.bf16_bits_to_f64(rhs[e]), (), (), (1,), (0,))
+        check(to_f64(out[e, torch.from_numpy(rows).cuda()].contiguous()), ref, f"ECH,EHM->ECM expert {e}")

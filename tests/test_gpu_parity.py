@@ -265,6 +265,25 @@ def test_two_contracting_dims_and_batch_fp32():
         check(st.out_shard(pid), ref, fro_tol=1e-5)
 
 
+def test_second_layer_einsums_small():
+    # BSH,HM->BSM with H split over 4 partitions (uneven: 1000/4 = 250, rows padded to 256) and bf16 output of the sum
+    w = wl.ffn_second(B=3, S=70, H=1000, M=264, Y=4)
+    lhs, rhs = wl.draw_normal_bf16(1, w.lhs_shape), wl.draw_normal_bf16(2, w.rhs_shape, 0.05)
+    st = Staged(w, lhs, rhs, row_align=8)
+    assert g.classify_dot(st.mesh, st.dims, st.lhs_sh, st.rhs_sh, st.out_sh) == (g.AXIS_CONTRACTING,)
+    st.run_grouped()
+    ref = oracle_global(w, lhs, rhs)
+    for pid in range(4):
+        check(st.out_shard(pid), ref, what=f"BSH,HM->BSM pid {pid}")
+    # ECH,EHM->ECM with fill counts
+    w = wl.moe_second(E=3, C=200, H=520, M=264)
+    fill = w.draw_fill()
+    lhs, rhs = wl.draw_normal_bf16(1, w.lhs_shape), wl.draw_normal_bf16(2, w.rhs_shape, 0.05)
+    st = Staged(w, lhs, rhs, row_align=8)
+    st.run_grouped(fill=fill)
+    compare_all_shards(st, w, oracle_global(w, lhs, rhs, fill=fill))
+
+
 def test_needs_reshard_and_bad_arguments_on_device_calls():
     w = wl.mesh2d(M=64, K=64, N=64, X=2, Y=2, cfg=7)
     lhs, rhs = wl.draw_normal_bf16(1, w.lhs_shape), wl.draw_normal_bf16(2, w.rhs_shape)

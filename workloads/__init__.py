@@ -234,5 +234,27 @@ def mesh2d_uneven() -> DotWorkload:
 
 
 
+def ffn_second(B: int = 8, S: int = 2048, H: int = 32768, M: int = 8192, Y: int = 4) -> DotWorkload:
+    """Second feed-forward einsum BSH,HM->BSM with H split over Y partitions (Section 5.1, Table 1): every partition
+    contracts its H slice and holds a partial BSM that the AllReduce / ReduceScatter sums."""
+    return DotWorkload(
+        name="ffn_bsh_hm", cfg=7, dtype="bf16", out_dtype="bf16",
+        lhs_shape=(B, S, H), rhs_shape=(H, M),
+        lhs_batch=(), rhs_batch=(), lhs_contract=(2,), rhs_contract=(0,),
+        mesh_shape=(Y,), device_ids=_ids(Y),
+        lhs_map=(-1, -1, 0), rhs_map=(0, -1), out_map=(-1, -1, -1), einsum="BSH,HM->BSM")
+
+
+def moe_second(E: int = 4, C: int = 1024, H: int = 32768, M: int = 8192) -> DotWorkload:
+    """Second expert einsum ECH,EHM->ECM on one device's share (Section 5.4), with per-expert fill counts."""
+    return DotWorkload(
+        name="moe_ech_ehm", cfg=8, dtype="bf16", out_dtype="bf16",
+        lhs_shape=(E, C, H), rhs_shape=(E, H, M),
+        lhs_batch=(0,), rhs_batch=(0,), lhs_contract=(2,), rhs_contract=(1,),
+        mesh_shape=(1,), device_ids=(0,),
+        lhs_map=(0, -1, -1), rhs_map=(0, -1, -1), out_map=(0, -1, -1),
+        fill_range=(C // 2, C), einsum="ECH,EHM->ECM")
+
+
 def all_configs() -> List[DotWorkload]:
     return [tiny_1d(), ffn(), ksplit(), moe(), mesh2d()]
