@@ -118,6 +118,17 @@ int32_t gspmd_classify_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
                            const gspmd_sharding* lhs_sh, const gspmd_sharding* rhs_sh,
                            const gspmd_sharding* out_sh, int32_t* axis_class);
 
+/* Output sharding of a Dot merged from the operand shardings (sharding propagation through Dot, Section 3.5):
+ * an out dimension inherits the mesh dimension of the operand dimension it comes from, so that for every device
+ * Offset(out, d, i) equals the operand's offset on every inherited sharded dimension; a mesh dimension that splits
+ * a contracting pair leaves the output unsplit on it (a partial sum).  GSPMD_ERR_NEEDS_RESHARD if the operand
+ * shardings are not compatible (a batch or contracting pair split differently on the two sides, one mesh dimension on
+ * both a lhs and a rhs non-contracting dimension).  out_mapping / out_shape: host arrays of (n_batch + lhs free +
+ * rhs free) entries, out_shape may be NULL; out_rank (nullable) receives the rank.  Pure host work. */
+int32_t gspmd_infer_out_sharding(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
+                                 const gspmd_sharding* lhs_sh, const gspmd_sharding* rhs_sh,
+                                 int32_t* out_mapping, int64_t* out_shape, int32_t* out_rank);
+
 /* One strided GEMM of the list a partition's local Dot is lowered to:
  *   C[m, n] = sum_k A[m, k] * B[k, n]   for m < m_valid, n < n_valid, k < k_valid,   C = 0 on the rest of
  *   [m_static, n_static];  A[m,k] at lhs element a_offset + m*lda + k, B[k,n] at rhs element b_offset + k*ldb + n,

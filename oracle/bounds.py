@@ -80,3 +80,29 @@ def shard_bounds(mesh_shape: Sequence[int], device_ids: Sequence[int],
         valid.append(max(0, min(per, size - off)))
         shard.append(per)
     return tuple(offset), tuple(valid), tuple(shard)
+
+
+def is_merged_sharding(mesh_shape, device_ids, out_shape, out_map, inherited) -> bool:
+    """Whether `out_map` is a merged sharding in the sense of Section 3.5.
+
+    `inherited` lists (out_dim, operand_shape, operand_map, operand_dim): out dimension out_dim comes from that
+    operand dimension.  The definition: for every device d and every *sharded* operand dimension i,
+    Offset(S, d, i) == Offset(S_operand, d, i); and S splits no dimension the operands do not split.
+    """
+    total = 1
+    for s in mesh_shape:
+        total *= s
+    sharded_out = set()
+    for out_dim, op_shape, op_map, op_dim in inherited:
+        if op_map[op_dim] == -1 or mesh_shape[op_map[op_dim]] == 1:
+            continue
+        sharded_out.add(out_dim)
+        for d in range(total):
+            o_off, _, _ = shard_bounds(mesh_shape, device_ids, out_shape, out_map, d)
+            p_off, _, _ = shard_bounds(mesh_shape, device_ids, op_shape, op_map, d)
+            if o_off[out_dim] != p_off[op_dim]:
+                return False
+    for i, a in enumerate(out_map):
+        if a != -1 and mesh_shape[a] > 1 and i not in sharded_out:
+            return False
+    return True

@@ -8,6 +8,6 @@ from .binding import (  # noqa: F401
     AXIS_BATCH, AXIS_CONTRACTING, AXIS_LHS_FREE, AXIS_RHS_FREE, AXIS_UNUSED,
     BF16, F32, DotDims, GspmdError, Mesh, Sharding, ShardBuf,
     classify_dot, dot_workspace_bytes, grouped_dot, library_path, load_library,
-    local_dot, plan_dot, reduce_partials, shard_assemble, shard_bounds, shard_extract,
+    infer_out_sharding, local_dot, plan_dot, reduce_partials, shard_assemble, shard_bounds, shard_extract,
     status_string, EXPORTED_SYMBOLS,
 )

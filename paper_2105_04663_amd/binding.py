@@ -12,7 +12,7 @@ AXIS_UNUSED, AXIS_BATCH, AXIS_LHS_FREE, AXIS_RHS_FREE, AXIS_CONTRACTING = range(
 EXPORTED_SYMBOLS = (
     "gspmd_status_string", "gspmd_shard_bounds", "gspmd_classify_dot", "gspmd_dot_workspace_bytes",
     "gspmd_local_dot", "gspmd_grouped_dot", "gspmd_reduce_partials", "gspmd_shard_extract",
-    "gspmd_shard_assemble", "gspmd_plan_dot",
+    "gspmd_shard_assemble", "gspmd_plan_dot", "gspmd_infer_out_sharding",
 )
 
 
@@ -74,6 +74,7 @@ def load_library():
     lib.gspmd_reduce_partials.argtypes = [C.POINTER(C.c_void_p), C.c_int32, C.c_int64, C.c_void_p, C.c_int32, C.c_void_p]
     lib.gspmd_shard_extract.argtypes = [pm, ps, C.c_int64, C.c_void_p, pb, C.c_uint32, C.c_void_p]
     lib.gspmd_shard_assemble.argtypes = [pm, ps, C.c_int64, pb, C.c_void_p, C.c_void_p]
+    lib.gspmd_infer_out_sharding.argtypes = [pm, pd, ps, ps, pi32, pi64, pi32]
     lib.gspmd_plan_dot.argtypes = [pm, pd, ps, ps, ps, C.c_int64, C.c_int64, C.c_int64, C.c_int64, pi64,
                                    C.POINTER(_CGemmDesc), C.c_int64, pi64]
     for name in EXPORTED_SYMBOLS[1:]:
@@ -197,6 +198,16 @@ def dot_workspace_bytes(mesh: Mesh, dims: DotDims, lhs_sh: Sharding, rhs_sh: Sha
     _check(load_library().gspmd_dot_workspace_bytes(C.byref(m), C.byref(d), C.byref(a), C.byref(b), C.byref(o),
                                                     int(partition_id), int(has_fill), C.byref(n)), "gspmd_dot_workspace_bytes")
     return int(n.value)
+
+
+def infer_out_sharding(mesh: Mesh, dims: DotDims, lhs_sh: Sharding, rhs_sh: Sharding) -> Sharding:
+    """Output sharding merged from the operand shardings (Section 3.5)."""
+    m, d, a, b = mesh._c(), dims._c(), lhs_sh._c(), rhs_sh._c()
+    cap = len(lhs_sh.global_shape) + len(rhs_sh.global_shape) + 1
+    mapping, shape, rank = (C.c_int32 * cap)(), (C.c_int64 * cap)(), C.c_int32(0)
+    _check(load_library().gspmd_infer_out_sharding(C.byref(m), C.byref(d), C.byref(a), C.byref(b), mapping, shape,
+                                                   C.byref(rank)), "gspmd_infer_out_sharding")
+    return Sharding(tuple(shape[:rank.value]), tuple(mapping[:rank.value]))
 
 
 def plan_dot(mesh: Mesh, dims: DotDims, lhs_sh: Sharding, rhs_sh: Sharding, out_sh: Sharding, partition_id: int,

@@ -156,6 +156,72 @@ int32_t gspmd_classify_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
   return GSPMD_OK;
 }
 
+int32_t gspmd_infer_out_sharding(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
+                                 const gspmd_sharding* lhs_sh, const gspmd_sharding* rhs_sh,
+                                 int32_t* out_mapping, int64_t* out_shape, int32_t* out_rank) {
+  if (!out_mapping || !dims) return GSPMD_ERR_NULL;
+  int32_t st = validate_mesh(mesh, nullptr);
+  if (st != GSPMD_OK) return st;
+  if ((st = validate_sharding(mesh, lhs_sh)) != GSPMD_OK || (st = validate_sharding(mesh, rhs_sh)) != GSPMD_OK) return st;
+  // a provisional, unsplit output lets analyse_dot check the dimension numbers and name the roles
+  const int nb = dims->n_batch, nc = dims->n_contract;
+  if (nb < 0 || nc < 0 || nb + nc > lhs_sh->rank || nb + nc > rhs_sh->rank) return GSPMD_ERR_BAD_DOT_DIMS;
+  const int rank = lhs_sh->rank + rhs_sh->rank - nb - 2 * nc;
+  if (rank <= 0 || rank > kMaxRank) return GSPMD_ERR_UNSUPPORTED;
+  int64_t shape[kMaxRank];
+  int32_t map[kMaxRank];
+  std::vector<bool> lused(static_cast<size_t>(lhs_sh->rank), false), rused(static_cast<size_t>(rhs_sh->rank), false);
+  for (int i = 0; i < nb; ++i) {
+    const int a = dims->lhs_batch ? dims->lhs_batch[i] : -1, b = dims->rhs_batch ? dims->rhs_batch[i] : -1;
+    if (a < 0 || a >= lhs_sh->rank || b < 0 || b >= rhs_sh->rank) return GSPMD_ERR_BAD_DOT_DIMS;
+    lused[static_cast<size_t>(a)] = rused[static_cast<size_t>(b)] = true;
+  }
+  for (int i = 0; i < nc; ++i) {
+    const int a = dims->lhs_contract ? dims->lhs_contract[i] : -1, b = dims->rhs_contract ? dims->rhs_contract[i] : -1;
+    if (a < 0 || a >= lhs_sh->rank || b < 0 || b >= rhs_sh->rank) return GSPMD_ERR_BAD_DOT_DIMS;
+    lused[static_cast<size_t>(a)] = rused[static_cast<size_t>(b)] = true;
+  }
+  int n = 0;
+  for (int i = 0; i < nb; ++i) { shape[n] = lhs_sh->global_shape[dims->lhs_batch[i]]; map[n++] = -1; }
+  for (int i = 0; i < lhs_sh->rank; ++i) if (!lused[static_cast<size_t>(i)]) { shape[n] = lhs_sh->global_shape[i]; map[n++] = -1; }
+  for (int i = 0; i < rhs_sh->rank; ++i) if (!rused[static_cast<size_t>(i)]) { shape[n] = rhs_sh->global_shape[i]; map[n++] = -1; }
+  if (n != rank) return GSPMD_ERR_BAD_DOT_DIMS;
+  gspmd_sharding out{rank, shape, map};
+  DotRoles r;
+  // roles and size checks only: run the analysis on a 1-partition mesh so that no pattern is rejected yet
+  const int64_t one = 1, zero = 0;
+  gspmd_mesh unit{1, &one, &zero};
+  std::vector<int32_t> lm(static_cast<size_t>(lhs_sh->rank), -1), rm(static_cast<size_t>(rhs_sh->rank), -1);
+  gspmd_sharding l1{lhs_sh->rank, lhs_sh->global_shape, lm.data()}, r1{rhs_sh->rank, rhs_sh->global_shape, rm.data()};
+  if ((st = analyse_dot(&unit, dims, &l1, &r1, &out, &r, nullptr)) != GSPMD_OK) return st;
+  for (int a = 0; a < mesh->rank; ++a) {
+    if (mesh->shape[a] == 1) continue;                // splits nothing
+    int ld = -1, rd = -1;
+    for (int i = 0; i < lhs_sh->rank; ++i) if (lhs_sh->dims_mapping[i] == a) ld = i;
+    for (int i = 0; i < rhs_sh->rank; ++i) if (rhs_sh->dims_mapping[i] == a) rd = i;
+    if (ld < 0 && rd < 0) continue;
+    auto idx = [](const int* list, int cnt, int v) { for (int i = 0; i < cnt; ++i) if (list[i] == v) return i; return -1; };
+    const int lb = ld >= 0 ? idx(r.lhs_batch, r.nb, ld) : -1, rbb = rd >= 0 ? idx(r.rhs_batch, r.nb, rd) : -1;
+    const int lcn = ld >= 0 ? idx(r.lhs_contract, r.nc, ld) : -1, rcn = rd >= 0 ? idx(r.rhs_contract, r.nc, rd) : -1;
+    const int lf = ld >= 0 ? idx(r.lhs_free, r.nlf, ld) : -1, rf = rd >= 0 ? idx(r.rhs_free, r.nrf, rd) : -1;
+    if (lb >= 0 || rbb >= 0) {                        // a batch pair must be split alike on both sides
+      if (lb < 0 || rbb != lb) return GSPMD_ERR_NEEDS_RESHARD;
+      map[lb] = a;
+    } else if (lcn >= 0 || rcn >= 0) {                // so must a contracting pair; the output is a partial sum
+      if (lcn < 0 || rcn != lcn) return GSPMD_ERR_NEEDS_RESHARD;
+    } else if (lf >= 0 && rf >= 0) {                  // one mesh dimension cannot split two output dimensions
+      return GSPMD_ERR_NEEDS_RESHARD;
+    } else if (lf >= 0) {
+      map[r.nb + lf] = a;
+    } else {
+      map[r.nb + r.nlf + rf] = a;
+    }
+  }
+  for (int i = 0; i < rank; ++i) { out_mapping[i] = map[i]; if (out_shape) out_shape[i] = shape[i]; }
+  if (out_rank) *out_rank = rank;
+  return GSPMD_OK;
+}
+
 int32_t gspmd_plan_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
                        const gspmd_sharding* lhs_sh, const gspmd_sharding* rhs_sh, const gspmd_sharding* out_sh,
                        int64_t lhs_row_stride, int64_t rhs_row_stride, int64_t out_row_stride,
