@@ -8,8 +8,8 @@ A step is one pass of the hot path over the Transformer feed-forward share
 shard bounds + dot classification + problem planning on the host and the fused
 pad/mask + MFMA contraction + epilogue on the GPU, through the C ABI's grouped entry
 point, inputs resident in HBM.  Prints ONE JSON line.  The other benchmark configs
-(contracting split with on-GPU reduce, MoE experts, 4x8 nested mesh) are timed the same
-way and reported under "others".  The CPU oracle is timed on a bounded row sample of the
+(contracting split with on-GPU reduce, MoE experts, 4x8 nested mesh), the second einsum of each layer
+and the backward contractions of the feed-forward layer are timed the same way and reported under "others".  The CPU oracle is timed on a bounded row sample of the
 same workload and its result is compared with the GPU output of those rows.
 """
 from __future__ import annotations
@@ -193,7 +193,7 @@ def main():
     # ------------------------------------------------------------------ the other configs
     if not args.headline_only:
         others = {}
-        for make in (wl.ksplit, wl.moe, wl.mesh2d, wl.ffn_second, wl.moe_second):
+        for make in (wl.ksplit, wl.moe, wl.mesh2d, wl.ffn_second, wl.moe_second, wl.ffn_wgrad, wl.ffn_dgrad):
             ww = make()
             s2 = Staged(ww)
             wall, ev = timed(s2, max(10, args.steps // 2), max(3, args.warmup // 2))

@@ -129,16 +129,24 @@ int32_t gspmd_infer_out_sharding(const gspmd_mesh* mesh, const gspmd_dot_dims* d
                                  const gspmd_sharding* lhs_sh, const gspmd_sharding* rhs_sh,
                                  int32_t* out_mapping, int64_t* out_shape, int32_t* out_rank);
 
+/* Which index of a lowered GEMM's operand is the contiguous one; follows from where the Dot's contracting
+ * dimensions sit in each operand.  0 = the forward einsums (lhs "...,c", rhs "c,..."). */
+typedef enum {
+  GSPMD_LAYOUT_LHS_K_MAJOR = 1,       /* lhs non-contracting dimension last:  A[m,k] at a_offset + k*lda + m */
+  GSPMD_LAYOUT_RHS_K_CONTIGUOUS = 2   /* rhs contracting dimension last:      B[k,n] at b_offset + n*ldb + k */
+} gspmd_layout_bits;
+
 /* One strided GEMM of the list a partition's local Dot is lowered to:
  *   C[m, n] = sum_k A[m, k] * B[k, n]   for m < m_valid, n < n_valid, k < k_valid,   C = 0 on the rest of
- *   [m_static, n_static];  A[m,k] at lhs element a_offset + m*lda + k, B[k,n] at rhs element b_offset + k*ldb + n,
+ *   [m_static, n_static];  A[m,k] at lhs element a_offset + m*lda + k, B[k,n] at rhs element b_offset + k*ldb + n
+ *   (the roles of the two indices exchanged where `layout` has the operand's gspmd_layout_bits bit set),
  *   C[m,n] at out element c_offset + m*ldc + n (offsets in elements from the shard buffers' data pointers). */
 typedef struct {
   int64_t a_offset, b_offset, c_offset;
   int64_t lda, ldb, ldc;
   int32_t m_valid, n_valid, k_valid;
   int32_t m_static, n_static;
-  int32_t reserved;
+  int32_t layout;
 } gspmd_gemm_desc;
 
 /* How gspmd_local_dot lowers partition `partition_id`'s Dot (shard bounds -> flattened batch / free / contracting
@@ -164,8 +172,10 @@ int32_t gspmd_dot_workspace_bytes(const gspmd_mesh* mesh, const gspmd_dot_dims* 
  *   out[b.., i.., j..] = sum_c lhs[b.., i.., c..] * rhs[b.., c.., j..]   over the partition's VALID extents,
  * fp32 accumulation, operands bf16 (out bf16 or f32) or f32 (out f32).
  * lhs/rhs/out: the partition's shard buffers (static shard shapes under lhs_sh/rhs_sh/out_sh).
- * Layout: batch dims leading (same order), lhs contracting dims trailing, rhs contracting dims
- * right after batch; anything else is GSPMD_ERR_UNSUPPORTED.
+ * Dimension order: the last dimension of each operand must be its innermost contracting or its
+ * innermost non-contracting dimension, and the contracting dimensions must nest alike in both
+ * operands (forward einsums "..c x c..", weight gradients "c.. x c..", input gradients
+ * "..c x ..c" all qualify); anything else is GSPMD_ERR_UNSUPPORTED.
  * Positions >= valid length are masked to 0 in both operands along contracting dims and never
  * read along any dim (Section 4.1); out's padded region is written as 0.
  * If a mesh dimension is GSPMD_AXIS_CONTRACTING, out must be f32 and receives this

@@ -6,7 +6,7 @@ missing library raises.
 """
 from .binding import (  # noqa: F401
     AXIS_BATCH, AXIS_CONTRACTING, AXIS_LHS_FREE, AXIS_RHS_FREE, AXIS_UNUSED,
-    BF16, F32, DotDims, GspmdError, Mesh, Sharding, ShardBuf,
+    BF16, F32, LAYOUT_LHS_K_MAJOR, LAYOUT_RHS_K_CONTIGUOUS, DotDims, GspmdError, Mesh, Sharding, ShardBuf,
     classify_dot, dot_workspace_bytes, grouped_dot, library_path, load_library,
     infer_out_sharding, local_dot, plan_dot, reduce_partials, shard_assemble, shard_bounds, shard_extract,
     status_string, EXPORTED_SYMBOLS,

@@ -8,6 +8,7 @@ from typing import List, Optional, Sequence, Tuple
 
 F32, BF16 = 0, 1
 AXIS_UNUSED, AXIS_BATCH, AXIS_LHS_FREE, AXIS_RHS_FREE, AXIS_CONTRACTING = range(5)
+LAYOUT_LHS_K_MAJOR, LAYOUT_RHS_K_CONTIGUOUS = 1, 2
 
 EXPORTED_SYMBOLS = (
     "gspmd_status_string", "gspmd_shard_bounds", "gspmd_classify_dot", "gspmd_dot_workspace_bytes",
@@ -43,7 +44,7 @@ class _CGemmDesc(C.Structure):
     _fields_ = [("a_offset", C.c_int64), ("b_offset", C.c_int64), ("c_offset", C.c_int64),
                 ("lda", C.c_int64), ("ldb", C.c_int64), ("ldc", C.c_int64),
                 ("m_valid", C.c_int32), ("n_valid", C.c_int32), ("k_valid", C.c_int32),
-                ("m_static", C.c_int32), ("n_static", C.c_int32), ("reserved", C.c_int32)]
+                ("m_static", C.c_int32), ("n_static", C.c_int32), ("layout", C.c_int32)]
 
 
 _LIB = None
@@ -221,7 +222,7 @@ def plan_dot(mesh: Mesh, dims: DotDims, lhs_sh: Sharding, rhs_sh: Sharding, out_
     _check(lib.gspmd_plan_dot(*args, None, 0, C.byref(n)), "gspmd_plan_dot")
     arr = (_CGemmDesc * max(1, n.value))()
     _check(lib.gspmd_plan_dot(*args, arr, n.value, C.byref(n)), "gspmd_plan_dot")
-    return [{f: getattr(arr[i], f) for f, _ in _CGemmDesc._fields_ if f != "reserved"} for i in range(n.value)]
+    return [{f: getattr(arr[i], f) for f, _ in _CGemmDesc._fields_} for i in range(n.value)]
 
 
 def _fill(fill):

@@ -21,13 +21,21 @@ tile 2u+4 during the MFMA phase of step u, group 1 tile 2u+5.  With five stages 
 phase (>= 1024 cycles) plus the slack of a read phase to land; s_waitcnt vmcnt sits right before the barrier that
 publishes the tile.
 
+Operand layouts.  Each operand's LDS tile keeps the operand's own memory order, so there are two tile formats:
+K-contiguous ([256 rows][32 k], fragment = one ds_read_b128) and K-major ([32 k][256 columns], fragment = two
+ds_read_b64_tr_b16, block b of 16 columns at address ^ (b << 5)).  The forward einsums have a K-contiguous lhs and a
+K-major rhs; a weight gradient has both K-major, an input gradient both K-contiguous.  One set of macros is written
+per combination (GSPMD_MAINLOOP_L<layout>_..., layout bit 0 = lhs K-major, bit 1 = rhs K-contiguous); only the read
+phase differs (32, 48, 24 or 40 LDS reads into the same 96 fragment registers).
+
 Register plan per wave: v[0:127] accumulators acc(bm, bn) = v[4*(4*bm+bn) ..+3] (bm = 16-row block 0..7 of the
 wave's 128 rows, bn = 16-column block 0..3 of its 64 columns); fragments of tile q (0/1) of the K step:
 A fa_q[bm] = v[128+48q+4bm ..+3], B fb_q[bn] = v[160+48q+4bn ..+3]; v224 A read address, v225..v228 B read
-addresses (per bn) in the stage being read.
+addresses (per bn) in the stage being read, v229/v230 A read addresses of blocks 1..7 of a K-major lhs (an LDS read
+takes its address when it issues, so the two registers alternate).
 SGPRs: s[40:41]/s[42:43] pointers to the next A/B tile this group loads, s44 this wave's LDS write base (stage 0),
 s45 K steps left, s46 pointer advances left (the pointers stop at the last full tile: loads issued past it re-read
-that tile into a stage nobody reads any more), s47 B pointer step in bytes (two tiles), s52 write-stage offset,
+that tile into a stage nobody reads any more), s47/s54 B/A pointer step in bytes (two tiles), s52 write-stage offset,
 s53 read-stage offset, s48-s51 temporaries.
 """
 import sys
@@ -43,9 +51,11 @@ def acc(bm, bn):
     return f"v[{b}:{b + 3}]"
 
 
-def fa(q, bm):
+def fa(q, bm, half=None):
     b = 128 + 48 * q + 4 * bm
-    return f"v[{b}:{b + 3}]"
+    if half is None:
+        return f"v[{b}:{b + 3}]"
+    return f"v[{b + 2 * half}:{b + 2 * half + 1}]"
 
 
 def fb(q, bn, half=None):
@@ -55,21 +65,34 @@ def fb(q, bn, half=None):
     return f"v[{b + 2 * half}:{b + 2 * half + 1}]"
 
 
-def read_addrs():
-    return ["v_add_u32 v224, s53, %[ard]",
-            "v_add_u32 v225, s53, %[brd]",
-            "v_xor_b32 v226, 32, v225",
-            "v_xor_b32 v227, 64, v225",
-            "v_xor_b32 v228, 0x60, v225"]
+def xor_const(dst, c, src):
+    return f"v_xor_b32 {dst}, {c if c <= 64 else hex(c)}, {src}"
 
 
-def ds_reads(q):
+def read_addrs(layout):
+    out = ["v_add_u32 v224, s53, %[ard]", "v_add_u32 v225, s53, %[brd]"]
+    if not layout & 2:  # K-major rhs: one address per 16-column block
+        out += [xor_const(f"v{225 + bn}", bn << 5, "v225") for bn in range(1, 4)]
+    return out
+
+
+def ds_reads(q, layout):
     out = []
     for bm in range(8):
-        out.append(f"ds_read_b128 {fa(q, bm)}, v224 offset:{bm * 1024}")
+        if layout & 1:      # K-major lhs: block bm at address ^ (bm << 5), formed in one of two alternating registers
+            reg = "v224" if bm == 0 else f"v{229 + (bm & 1)}"
+            if bm:
+                out.append(xor_const(reg, bm << 5, "v224"))
+            for rd in range(2):
+                out.append(f"ds_read_b64_tr_b16 {fa(q, bm, rd)}, {reg} offset:{rd * 2048}")
+        else:
+            out.append(f"ds_read_b128 {fa(q, bm)}, v224 offset:{bm * 1024}")
     for bn in range(4):
-        for rd in range(2):
-            out.append(f"ds_read_b64_tr_b16 {fb(q, bn, rd)}, v{225 + bn} offset:{rd * 2048}")
+        if layout & 2:
+            out.append(f"ds_read_b128 {fb(q, bn)}, v225 offset:{bn * 1024}")
+        else:
+            for rd in range(2):
+                out.append(f"ds_read_b64_tr_b16 {fb(q, bn, rd)}, v{225 + bn} offset:{rd * 2048}")
     return out
 
 
@@ -77,8 +100,9 @@ def step_stage(reg, n):
     return [f"s_add_u32 {reg}, {reg}, {STAGE * n}", f"s_sub_u32 s48, {reg}, {LDS}", f"s_cmp_ge_u32 {reg}, {LDS}", f"s_cselect_b32 {reg}, s48, {reg}"]
 
 
-def mem_phase():
-    return read_addrs() + ds_reads(0) + step_stage("s53", 1) + read_addrs() + ds_reads(1) + step_stage("s53", 1)
+def mem_phase(layout):
+    return (read_addrs(layout) + ds_reads(0, layout) + step_stage("s53", 1)
+            + read_addrs(layout) + ds_reads(1, layout) + step_stage("s53", 1))
 
 
 def load(j):
@@ -90,7 +114,7 @@ def load(j):
 def advance():
     """Next tile of this group (two tiles on), pointers frozen at the last full tile; next write stage."""
     return ["s_cmp_lg_u32 s46, 0",
-            "s_cselect_b32 s50, 128, 0",
+            "s_cselect_b32 s50, s54, 0",
             "s_cselect_b32 s51, s47, 0",
             "s_cselect_b32 s48, 1, 0",
             "s_sub_u32 s46, s46, s48",
@@ -113,18 +137,18 @@ def mfma_phase(w):
     return out
 
 
-def group0(w):
+def group0(w, layout):
     """Waves 0-3: read phase of K step u, barrier, MFMA phase of u (loading tile 2u+4), barrier."""
-    s = ["L0_top_%=:"] + mem_phase() + ["s_waitcnt lgkmcnt(0)", "s_barrier"]
+    s = ["L0_top_%=:"] + mem_phase(layout) + ["s_waitcnt lgkmcnt(0)", "s_barrier"]
     s += mfma_phase(w)
     s += ["s_waitcnt vmcnt(8)", "s_barrier",
           "s_sub_u32 s45, s45, 1", "s_cmp_lg_u32 s45, 0", "s_cbranch_scc1 L0_top_%=", "s_nop 15", "s_nop 15"]
     return s
 
 
-def group1(w):
+def group1(w, layout):
     """Waves 4-7: one phase behind group 0 (extra barrier first); loads tile 2u+5 in its MFMA phase."""
-    s = ["s_barrier", "L1_top_%=:"] + mem_phase() + ["s_waitcnt vmcnt(0) lgkmcnt(0)", "s_barrier"]
+    s = ["s_barrier", "L1_top_%=:"] + mem_phase(layout) + ["s_waitcnt vmcnt(0) lgkmcnt(0)", "s_barrier"]
     s += mfma_phase(w)
     s += ["s_sub_u32 s45, s45, 1", "s_cmp_lg_u32 s45, 0", "s_cbranch_scc0 L1_end_%=",
           "s_barrier", "s_branch L1_top_%=", "L1_end_%=:", "s_nop 15", "s_nop 15"]
@@ -136,11 +160,12 @@ def macro(name, lines):
 
 
 def main():
-    clob = ", ".join(f'"v{i}"' for i in range(128, 229))
+    clob = ", ".join(f'"v{i}"' for i in range(128, 231))
     out = ["// Generated by gen_mainloop.py -- do not edit by hand.", "#pragma once"]
-    for w in range(4):
-        out.append(macro(f"GSPMD_MAINLOOP_G0_W{w}", group0(w)))
-        out.append(macro(f"GSPMD_MAINLOOP_G1_W{w}", group1(w)))
+    for layout in range(4):
+        for w in range(4):
+            out.append(macro(f"GSPMD_MAINLOOP_L{layout}_G0_W{w}", group0(w, layout)))
+            out.append(macro(f"GSPMD_MAINLOOP_L{layout}_G1_W{w}", group1(w, layout)))
     out.append(f'#define GSPMD_MAINLOOP_CLOBBERS {clob}, "s48", "s49", "s50", "s51", "m0", "scc", "vcc", "memory"')
     sys.stdout.write("\n".join(out) + "\n")
 

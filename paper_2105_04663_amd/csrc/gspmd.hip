@@ -39,19 +39,22 @@ int64_t assign_tiles(std::vector<Problem>& ps, int bm, int bn) {
   return t;
 }
 
-bool mfma_eligible(const std::vector<Problem>& ps, int32_t in_dtype) {
+bool mfma_eligible(const std::vector<Problem>& ps, int32_t in_dtype, int32_t layout) {
   if (in_dtype != GSPMD_BF16) return false;
+  // 32-bit byte offsets inside a tile: 256 rows of a K-contiguous operand, 32 of a K-major one
+  const int32_t max_lda = (layout & GSPMD_LAYOUT_LHS_K_MAJOR) ? (1 << 24) : (1 << 22);
+  const int32_t max_ldb = (layout & GSPMD_LAYOUT_RHS_K_CONTIGUOUS) ? (1 << 22) : (1 << 24);
   for (const auto& p : ps) {
     if (p.Kv == 0) continue;
     if ((reinterpret_cast<uintptr_t>(p.A) | reinterpret_cast<uintptr_t>(p.B)) & 15) return false;
     if ((p.lda & 7) || (p.ldb & 7)) return false;
-    if (p.lda > (1 << 22) || p.ldb > (1 << 24)) return false;   // 32-bit byte offsets inside a tile
+    if (p.lda > max_lda || p.ldb > max_ldb) return false;
   }
   return true;
 }
 
 // Upload the problem table into the workspace and launch the contraction over all tiles.
-int32_t launch_problems(std::vector<Problem>& ps, int32_t in_dtype, int32_t out_dtype,
+int32_t launch_problems(std::vector<Problem>& ps, int32_t layout, int32_t in_dtype, int32_t out_dtype,
                         void* workspace, int64_t workspace_bytes, hipStream_t stream) {
   // problems with an empty static output block write nothing
   ps.erase(std::remove_if(ps.begin(), ps.end(), [](const Problem& p) { return p.Ms == 0 || p.Ns == 0; }), ps.end());
@@ -60,7 +63,7 @@ int32_t launch_problems(std::vector<Problem>& ps, int32_t in_dtype, int32_t out_
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kWsAlign - 1)) || workspace_bytes < table_bytes)
     return GSPMD_ERR_WORKSPACE;
   if (in_dtype == GSPMD_F32 && out_dtype != GSPMD_F32) return GSPMD_ERR_UNSUPPORTED;
-  const bool mfma = mfma_eligible(ps, in_dtype);
+  const bool mfma = mfma_eligible(ps, in_dtype, layout);
   const int64_t tiles = mfma ? assign_tiles(ps, kMfmaBM, kMfmaBN) : assign_tiles(ps, kGenTile, kGenTile);
   if (tiles < 0) return GSPMD_ERR_UNSUPPORTED;
   if (hipMemcpyAsync(workspace, ps.data(), static_cast<size_t>(table_bytes), hipMemcpyHostToDevice, stream) != hipSuccess)
@@ -68,16 +71,16 @@ int32_t launch_problems(std::vector<Problem>& ps, int32_t in_dtype, int32_t out_
   const Problem* tab = static_cast<const Problem*>(workspace);
   const int n = static_cast<int>(ps.size());
   if (mfma) {
-    if (!launch_dot_mfma(tab, n, static_cast<int>(tiles), out_dtype, stream)) return GSPMD_ERR_DEVICE;
+    if (!launch_dot_mfma(tab, n, static_cast<int>(tiles), layout, out_dtype, stream)) return GSPMD_ERR_DEVICE;
     return GSPMD_OK;
   }
   const dim3 grid(static_cast<unsigned>(tiles)), block(256);
   if (in_dtype == GSPMD_F32)
-    hipLaunchKernelGGL((dot_fallback_kernel<float, float>), grid, block, 0, stream, tab, n);
+    hipLaunchKernelGGL((dot_fallback_kernel<float, float>), grid, block, 0, stream, tab, n, layout);
   else if (out_dtype == GSPMD_F32)
-    hipLaunchKernelGGL((dot_fallback_kernel<bf16_bits, float>), grid, block, 0, stream, tab, n);
+    hipLaunchKernelGGL((dot_fallback_kernel<bf16_bits, float>), grid, block, 0, stream, tab, n, layout);
   else
-    hipLaunchKernelGGL((dot_fallback_kernel<bf16_bits, bf16_bits>), grid, block, 0, stream, tab, n);
+    hipLaunchKernelGGL((dot_fallback_kernel<bf16_bits, bf16_bits>), grid, block, 0, stream, tab, n, layout);
   return hipGetLastError() == hipSuccess ? GSPMD_OK : GSPMD_ERR_DEVICE;
 }
 
@@ -240,7 +243,8 @@ int32_t gspmd_plan_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
   gspmd_shard_buf oc{reinterpret_cast<void*>(base_c), GSPMD_F32, out_row_stride};
   std::vector<Problem> ps;
   int64_t elems = 0;
-  if ((st = plan_partition(mesh, r, &la, lhs_sh, &rb, rhs_sh, &oc, out_sh, pid, lhs_fill, nullptr, &ps, &elems)) != GSPMD_OK) return st;
+  int32_t layout = 0;
+  if ((st = plan_partition(mesh, r, &la, lhs_sh, &rb, rhs_sh, &oc, out_sh, pid, lhs_fill, nullptr, &ps, &elems, &layout)) != GSPMD_OK) return st;
   *count = static_cast<int64_t>(ps.size());
   for (int64_t i = 0; i < std::min<int64_t>(capacity, *count); ++i) {
     const Problem& p = ps[static_cast<size_t>(i)];
@@ -251,7 +255,7 @@ int32_t gspmd_plan_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
     d.lda = p.lda; d.ldb = p.ldb; d.ldc = p.ldc;
     d.m_valid = p.Mv; d.n_valid = p.Nv; d.k_valid = p.Kv;
     d.m_static = p.Ms; d.n_static = p.Ns;
-    d.reserved = 0;
+    d.layout = layout;
   }
   return GSPMD_OK;
 }
@@ -295,11 +299,12 @@ int32_t gspmd_local_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
   if (has_contracting(mesh, cls) && out->dtype != GSPMD_F32) return GSPMD_ERR_UNSUPPORTED;
   std::vector<Problem> ps;
   int64_t elems = 0;
-  if ((st = plan_partition(mesh, r, lhs, lhs_sh, rhs, rhs_sh, out, out_sh, pid, lhs_fill, nullptr, &ps, &elems)) != GSPMD_OK)
+  int32_t layout = 0;
+  if ((st = plan_partition(mesh, r, lhs, lhs_sh, rhs, rhs_sh, out, out_sh, pid, lhs_fill, nullptr, &ps, &elems, &layout)) != GSPMD_OK)
     return st;
   for (const auto& p : ps)
     if ((p.Kv && (!p.A || !p.B)) || !p.C) return GSPMD_ERR_NULL;
-  return launch_problems(ps, lhs->dtype, out->dtype, workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
+  return launch_problems(ps, layout, lhs->dtype, out->dtype, workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
 }
 
 int32_t gspmd_grouped_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
@@ -350,6 +355,7 @@ int32_t gspmd_grouped_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
   // Partitions that hold the same operands and write the same buffer (replicas along an
   // unused mesh dimension) need the product only once.
   std::map<std::array<const void*, 3>, int64_t> done;
+  int32_t layout = 0;
   for (int64_t p = 0; p < P; ++p) {
     if (!contracting) {
       std::array<const void*, 3> key = {lhs_shards[p].data, rhs_shards[p].data, out_shards[p].data};
@@ -359,12 +365,12 @@ int32_t gspmd_grouped_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
     int64_t e = 0;
     const size_t before = ps.size();
     st = plan_partition(mesh, r, &lhs_shards[p], lhs_sh, &rhs_shards[p], rhs_sh, &out_shards[p], out_sh, p, lhs_fill,
-                        contracting ? partial[static_cast<size_t>(p)] : nullptr, &ps, &e);
+                        contracting ? partial[static_cast<size_t>(p)] : nullptr, &ps, &e, &layout);
     if (st != GSPMD_OK) return st;
     for (size_t i = before; i < ps.size(); ++i)
       if ((ps[i].Kv && (!ps[i].A || !ps[i].B)) || !ps[i].C) return GSPMD_ERR_NULL;
   }
-  st = launch_problems(ps, in_dtype, contracting ? GSPMD_F32 : out_dtype, workspace, workspace_bytes, stream);
+  st = launch_problems(ps, layout, in_dtype, contracting ? GSPMD_F32 : out_dtype, workspace, workspace_bytes, stream);
   if (st != GSPMD_OK || !contracting) return st;
 
   // Sum the partials of each reduce group (partitions that differ only along contracting

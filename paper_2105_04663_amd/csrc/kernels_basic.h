@@ -48,7 +48,7 @@ constexpr int kGenBK = 16;
 // Every load is predicated on the valid extents (masked positions contribute 0 and are never
 // read); stores cover the static extents and write 0 outside the valid region.
 template <typename TIn, typename TOut>
-__global__ __launch_bounds__(256) void dot_fallback_kernel(const Problem* __restrict__ tab, int n_prob) {
+__global__ __launch_bounds__(256) void dot_fallback_kernel(const Problem* __restrict__ tab, int n_prob, int layout) {
   __shared__ float As[kGenBK][kGenTile + 4];   // [k][m]
   __shared__ float Bs[kGenBK][kGenTile + 4];   // [k][n]
   const int tile = blockIdx.x;
@@ -65,6 +65,9 @@ __global__ __launch_bounds__(256) void dot_fallback_kernel(const Problem* __rest
 #pragma unroll
     for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
 
+  // element strides of the two indices of each operand
+  const int64_t a_sm = (layout & GSPMD_LAYOUT_LHS_K_MAJOR) ? 1 : P.lda, a_sk = (layout & GSPMD_LAYOUT_LHS_K_MAJOR) ? P.lda : 1;
+  const int64_t b_sk = (layout & GSPMD_LAYOUT_RHS_K_CONTIGUOUS) ? 1 : P.ldb, b_sn = (layout & GSPMD_LAYOUT_RHS_K_CONTIGUOUS) ? P.ldb : 1;
   if (m0 < P.Mv && n0 < P.Nv) {
     const int am = t >> 2, ak = (t & 3) * 4;     // A: row am, 4 consecutive k
     const int bk = t >> 4, bn = (t & 15) * 4;    // B: row bk, 4 consecutive n
@@ -72,9 +75,9 @@ __global__ __launch_bounds__(256) void dot_fallback_kernel(const Problem* __rest
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const int m = m0 + am, k = k0 + ak + j;
-        As[ak + j][am] = (m < P.Mv && k < P.Kv) ? load_as_float<TIn>(A + static_cast<int64_t>(m) * P.lda + k) : 0.f;
+        As[ak + j][am] = (m < P.Mv && k < P.Kv) ? load_as_float<TIn>(A + m * a_sm + k * a_sk) : 0.f;
         const int kk = k0 + bk, n = n0 + bn + j;
-        Bs[bk][bn + j] = (kk < P.Kv && n < P.Nv) ? load_as_float<TIn>(B + static_cast<int64_t>(kk) * P.ldb + n) : 0.f;
+        Bs[bk][bn + j] = (kk < P.Kv && n < P.Nv) ? load_as_float<TIn>(B + kk * b_sk + n * b_sn) : 0.f;
       }
       __syncthreads();
 #pragma unroll

@@ -1,5 +1,8 @@
-// bf16 MFMA contraction for gfx950 (CDNA4): C[m,n] = sum_k A[m,k] * B[k,n], A row-major with k
-// contiguous, B row-major with n contiguous ("NN"), fp32 accumulation in the matrix cores.
+// bf16 MFMA contraction for gfx950 (CDNA4): C[m,n] = sum_k A[m,k] * B[k,n], fp32 accumulation in the matrix
+// cores.  Each operand is either K-contiguous (rows of k) or K-major (rows of m resp. n); the forward einsums have
+// A K-contiguous and B K-major ("NN", described below), a weight gradient has both K-major, an input gradient both
+// K-contiguous.  The kernel is instantiated per combination (template parameter LAYOUT, GSPMD_LAYOUT_* bits): a
+// K-major A uses B's tile format and transpose reads, a K-contiguous B uses A's.
 //
 // Workgroup tile 256 x 256, 8 wavefronts (2 along m x 4 along n), each owning a 128 x 64 block as 8 x 4
 // v_mfma_f32_16x16x32_bf16 tiles (128 accumulator registers per lane), one workgroup per CU.
@@ -83,8 +86,41 @@ __device__ __forceinline__ int logical_tile(int b, int total) {
 
 constexpr int kBandRows = 8;
 
-template <typename TOut>
+// Per-lane byte offset, relative to the tile's base, of load instruction q (0..15) of a K-contiguous operand tile
+// ([256 rows][32 k]: instruction q covers rows 16q..16q+15, 4 lanes per row).  Rows past the valid extent reuse the
+// last valid row (their results are never stored).
+__device__ __forceinline__ int kc_load_offset(int q, int lane, int r0, int rows_valid, int ld) {
+  const int r = q * 16 + (lane >> 2);
+  const int c = (lane & 3) ^ swz_a(r);
+  const int rr = min(r0 + r, rows_valid - 1) - r0;
+  return (rr * ld + c * 8) * 2;
+}
+// Same for a K-major operand tile ([32 k][256 columns]: instruction q covers k rows 2q, 2q+1, 32 lanes per row).
+// 16-byte chunks past the valid extent reuse the last valid chunk.
+__device__ __forceinline__ int km_load_offset(int q, int lane, int c0, int cols_valid, int ld) {
+  const int kr = q * 2 + (lane >> 5);
+  const int cn = (lane & 31) ^ swz_b(kr);
+  int n = c0 + cn * 8;
+  if (n >= cols_valid) n = ((cols_valid - 1) >> 3) << 3;
+  return (kr * ld + (n - c0)) * 2;
+}
+// LDS byte offset (inside the operand's part of a stage) of a lane's fragment of 16-row block 0 whose first row is
+// `base`: K-contiguous tile, block b at + b * 1024.
+__device__ __forceinline__ int kc_frag_offset(int base, int lane) {
+  const int row = base + (lane & 15);
+  return row * 64 + (((lane >> 4) ^ swz_a(row)) << 4);
+}
+// K-major tile (read with the transpose read): block b at ^ (b << 5), second half of the fragment at + 4 * 512.
+__device__ __forceinline__ int km_frag_offset(int base, int lane) {
+  const int i = lane & 15;
+  const int krow = (lane >> 4) * 8 + (i >> 2);
+  const int cl = base + (i & 3) * 4;
+  return krow * 512 + (((cl >> 3) ^ swz_b(krow)) << 4) + (cl & 7) * 2;
+}
+
+template <typename TOut, int LAYOUT>
 __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const Problem* __restrict__ tab, int n_prob) {
+  constexpr bool AKM = (LAYOUT & GSPMD_LAYOUT_LHS_K_MAJOR) != 0, BKC = (LAYOUT & GSPMD_LAYOUT_RHS_K_CONTIGUOUS) != 0;
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   const int t = threadIdx.x, lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
@@ -108,33 +144,29 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const Problem* _
 
   const bool live = m0 < P.Mv && n0 < P.Nv && P.Kv > 0;
   if (live) {
-    const bf16_bits* __restrict__ Abase = static_cast<const bf16_bits*>(P.A) + static_cast<int64_t>(m0) * P.lda;
-    const bf16_bits* __restrict__ Bbase = static_cast<const bf16_bits*>(P.B) + n0;
+    // the tile's operand panels and the distance (elements) between consecutive 32-wide K tiles
+    const bf16_bits* __restrict__ Abase = static_cast<const bf16_bits*>(P.A) + (AKM ? static_cast<int64_t>(m0) : static_cast<int64_t>(m0) * P.lda);
+    const bf16_bits* __restrict__ Bbase = static_cast<const bf16_bits*>(P.B) + (BKC ? static_cast<int64_t>(n0) * P.ldb : static_cast<int64_t>(n0));
+    const int64_t a_tile = AKM ? static_cast<int64_t>(kMfmaBK) * P.lda : kMfmaBK;
+    const int64_t b_tile = BKC ? kMfmaBK : static_cast<int64_t>(kMfmaBK) * P.ldb;
     const int nk32 = P.Kv / kMfmaBK;          // full 32-wide K tiles
     const int nk64 = P.Kv / (2 * kMfmaBK);    // full 64-wide K steps (the assembly loop)
 
-    // ---- tile loads.  A tile (32 KiB) is 32 wave-instructions of 1 KiB (16 A: 16 rows x 64 B each, 16 B: 2 k-rows
-    // x 512 B each); the four waves of ONE group load a whole tile, wave wn taking A and B instructions 4*wn .. 4*wn+3.
+    // ---- tile loads.  A tile (32 KiB) is 32 wave-instructions of 1 KiB (16 per operand); the four waves of ONE
+    // group load a whole tile, wave wn taking instructions 4*wn .. 4*wn+3 of each operand.
     int a_off[4], b_off[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const int r = (wn * 4 + j) * 16 + (lane >> 2);
-      const int c = (lane & 3) ^ swz_a(r);
-      const int rr = min(m0 + r, P.Mv - 1) - m0;               // rows past the valid extent: reuse the last valid row
-      a_off[j] = (rr * P.lda + c * 8) * 2;      // bytes
-      const int kr = (wn * 4 + j) * 2 + (lane >> 5);
-      const int cn = (lane & 31) ^ swz_b(kr);
-      int n = n0 + cn * 8;
-      if (n >= P.Nv) n = ((P.Nv - 1) >> 3) << 3;               // chunks past the valid extent: reuse the last valid chunk
-      b_off[j] = (kr * P.ldb + (n - n0)) * 2;   // bytes
+      a_off[j] = AKM ? km_load_offset(wn * 4 + j, lane, m0, P.Mv, P.lda) : kc_load_offset(wn * 4 + j, lane, m0, P.Mv, P.lda);
+      b_off[j] = BKC ? kc_load_offset(wn * 4 + j, lane, n0, P.Nv, P.ldb) : km_load_offset(wn * 4 + j, lane, n0, P.Nv, P.ldb);
     }
     const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(smem));
     // this wave's 8 instructions of full tile kt; kt is clamped so that a load issued past the last full tile
     // re-reads a valid tile into a stage nobody reads any more
     auto load_tile = [&](int kt) {
       const int kc = min(kt, nk32 - 1);
-      const bf16_bits* ab = Abase + kc * kMfmaBK;
-      const bf16_bits* bb = Bbase + static_cast<int64_t>(kc) * kMfmaBK * P.ldb;
+      const bf16_bits* ab = Abase + kc * a_tile;
+      const bf16_bits* bb = Bbase + kc * b_tile;
       const uint32_t sa = lds0 + (kt % kNumStages) * kStage + wn * 4096;
 #pragma unroll
       for (int j = 0; j < 4; ++j) global_to_lds16(ab, a_off[j], sa + j * 1024);
@@ -143,56 +175,53 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const Problem* _
     };
     // a K tile that may be partial: through registers, zeroing what lies beyond the valid K in BOTH operands
     // (executed by the four waves of group 0)
+    auto tail_chunk = [&](bool kmajor, const bf16_bits* base, int off, int q, int k0) -> u32x4_t {
+      u32x4_t v = {0u, 0u, 0u, 0u};
+      if (kmajor) {         // a whole k row per 32 lanes
+        const int kr = k0 + q * 2 + (lane >> 5);
+        if (kr < P.Kv) v = *reinterpret_cast<const u32x4_t*>(reinterpret_cast<const unsigned char*>(base) + off);
+      } else {              // 8 consecutive k per lane
+        const int r = q * 16 + (lane >> 2);
+        const int k = k0 + ((lane & 3) ^ swz_a(r)) * 8;
+        if (k < P.Kv) {
+          v = *reinterpret_cast<const u32x4_t*>(reinterpret_cast<const unsigned char*>(base) + off);
+          if (k + 8 > P.Kv) v = mask_tail8(v, P.Kv - k);
+        }
+      }
+      return v;
+    };
     auto load_tail = [&](int kt, int stage) {
       const int k0 = kt * kMfmaBK;
-      const bf16_bits* ab = Abase + k0;
-      const bf16_bits* bb = Bbase + static_cast<int64_t>(k0) * P.ldb;
+      const bf16_bits* ab = Abase + kt * a_tile;
+      const bf16_bits* bb = Bbase + kt * b_tile;
       unsigned char* sa = smem + stage * kStage + wn * 4096 + lane * 16;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        const int r = (wn * 4 + j) * 16 + (lane >> 2);
-        const int k = k0 + ((lane & 3) ^ swz_a(r)) * 8;
-        u32x4_t v = {0u, 0u, 0u, 0u};
-        if (k < P.Kv) {
-          v = *reinterpret_cast<const u32x4_t*>(reinterpret_cast<const unsigned char*>(ab) + a_off[j]);
-          if (k + 8 > P.Kv) v = mask_tail8(v, P.Kv - k);
-        }
-        *reinterpret_cast<u32x4_t*>(sa + j * 1024) = v;
-        const int kr = k0 + (wn * 4 + j) * 2 + (lane >> 5);
-        u32x4_t w = {0u, 0u, 0u, 0u};
-        if (kr < P.Kv) w = *reinterpret_cast<const u32x4_t*>(reinterpret_cast<const unsigned char*>(bb) + b_off[j]);
-        *reinterpret_cast<u32x4_t*>(sa + kStageA + j * 1024) = w;
+        *reinterpret_cast<u32x4_t*>(sa + j * 1024) = tail_chunk(AKM, ab, a_off[j], wn * 4 + j, k0);
+        *reinterpret_cast<u32x4_t*>(sa + kStageA + j * 1024) = tail_chunk(!BKC, bb, b_off[j], wn * 4 + j, k0);
       }
       GSPMD_WAIT_ALL();
     };
-    // ---- fragment read offsets
-    int a_frag;      // + bm*16*64 added as an immediate
-    {
-      const int row = wm * 128 + (lane & 15);
-      a_frag = row * 64 + (((lane >> 4) ^ swz_a(row)) << 4);
-    }
-    int b_frag;      // block bn is at b_frag ^ (bn << 5); + rd*4*512 added as an immediate
-    {
-      const int i = lane & 15;
-      const int krow = (lane >> 4) * 8 + (i >> 2);
-      const int nl = wn * 64 + (i & 3) * 4;
-      b_frag = kStageA + krow * 512 + ((((nl >> 3)) ^ swz_b(krow)) << 4) + (nl & 7) * 2;
-    }
-    // fragment reads and MFMAs of one K tile in compiler-scheduled form (partial last tile only)
+    // ---- fragment read offsets inside a stage
+    const int a_frag = AKM ? km_frag_offset(wm * 128, lane) : kc_frag_offset(wm * 128, lane);
+    const int b_frag = kStageA + (BKC ? kc_frag_offset(wn * 64, lane) : km_frag_offset(wn * 64, lane));
+    // fragment reads and MFMAs of one K tile in compiler-scheduled form (what is left of K after the assembly loop)
     bf16x8_t fa[8], fb[4];
+    auto read_kc = [&](const unsigned char* p) {
+      return __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(p));
+    };
+    auto read_km = [&](const unsigned char* p) {
+      short8_t both;
+      both.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_t*)(p));
+      both.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_t*)(p + 4 * 512));
+      return __builtin_bit_cast(bf16x8_t, both);
+    };
     auto read_frags = [&](int stage) {
       const unsigned char* base = smem + stage * kStage;
 #pragma unroll
-      for (int bm = 0; bm < 8; ++bm)
-        fa[bm] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(base + a_frag + bm * 16 * 64));
+      for (int bm = 0; bm < 8; ++bm) fa[bm] = AKM ? read_km(base + (a_frag ^ (bm << 5))) : read_kc(base + a_frag + bm * 1024);
 #pragma unroll
-      for (int bn = 0; bn < 4; ++bn) {
-        const unsigned char* p = base + (b_frag ^ (bn << 5));
-        short8_t both;
-        both.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_t*)(p));
-        both.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_t*)(p + 4 * 512));
-        fb[bn] = __builtin_bit_cast(bf16x8_t, both);
-      }
+      for (int bn = 0; bn < 4; ++bn) fb[bn] = BKC ? read_kc(base + b_frag + bn * 1024) : read_km(base + (b_frag ^ (bn << 5)));
     };
     auto mma_all = [&]() {
 #pragma unroll
@@ -215,37 +244,42 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const Problem* _
       {   // ---- K loop over the full 64-wide steps: hand-scheduled assembly, see gen_mainloop.py for the register plan
         const uint32_t ard = lds0 + a_frag, brd = lds0 + b_frag;
         const int first = min(4 + wm, nk32 - 1);          // group 0 goes on with tiles 4, 6, ..; group 1 with 5, 7, ..
-        unsigned long long aptr = reinterpret_cast<unsigned long long>(Abase + first * kMfmaBK);
-        unsigned long long bptr = reinterpret_cast<unsigned long long>(Bbase + static_cast<int64_t>(first) * kMfmaBK * P.ldb);
+        unsigned long long aptr = reinterpret_cast<unsigned long long>(Abase + first * a_tile);
+        unsigned long long bptr = reinterpret_cast<unsigned long long>(Bbase + first * b_tile);
         uint32_t nadv = (nk32 - 1 - first) / 2;
         const uint32_t wrbase = lds0 + wn * 4096;
         uint32_t wstage = ((4 + wm) % kNumStages) * kStage, rstage = 0;
         uint32_t nkr = nk64;
-        const uint32_t bstep = static_cast<uint32_t>(P.ldb) * (2 * kMfmaBK * 2);
+        const uint32_t astep = static_cast<uint32_t>(a_tile) * 4, bstep = static_cast<uint32_t>(b_tile) * 4;   // two tiles, bytes
 #define GSPMD_MAINLOOP_OPERANDS \
         : "+{v[0:15]}"(acc[0]), "+{v[16:31]}"(acc[1]), "+{v[32:47]}"(acc[2]), "+{v[48:63]}"(acc[3]), \
           "+{v[64:79]}"(acc[4]), "+{v[80:95]}"(acc[5]), "+{v[96:111]}"(acc[6]), "+{v[112:127]}"(acc[7]), \
           "+{s[40:41]}"(aptr), "+{s[42:43]}"(bptr), "+{s45}"(nkr), "+{s46}"(nadv), "+{s52}"(wstage), "+{s53}"(rstage) \
         : [ard] "v"(ard), [brd] "v"(brd), [ao0] "v"(a_off[0]), [ao1] "v"(a_off[1]), [ao2] "v"(a_off[2]), [ao3] "v"(a_off[3]), \
-          [bo0] "v"(b_off[0]), [bo1] "v"(b_off[1]), [bo2] "v"(b_off[2]), [bo3] "v"(b_off[3]), "{s44}"(wrbase), "{s47}"(bstep) \
+          [bo0] "v"(b_off[0]), [bo1] "v"(b_off[1]), [bo2] "v"(b_off[2]), [bo3] "v"(b_off[3]), "{s44}"(wrbase), "{s47}"(bstep), "{s54}"(astep) \
         : GSPMD_MAINLOOP_CLOBBERS
         // the four waves of a group issue their tile loads after different MFMAs, so that the CU's
         // texture-address unit sees one load at a time
-        if (wm == 0) {
-          switch (wn) {
-            case 0: asm volatile(GSPMD_MAINLOOP_G0_W0 GSPMD_MAINLOOP_OPERANDS); break;
-            case 1: asm volatile(GSPMD_MAINLOOP_G0_W1 GSPMD_MAINLOOP_OPERANDS); break;
-            case 2: asm volatile(GSPMD_MAINLOOP_G0_W2 GSPMD_MAINLOOP_OPERANDS); break;
-            default: asm volatile(GSPMD_MAINLOOP_G0_W3 GSPMD_MAINLOOP_OPERANDS); break;
-          }
-        } else {
-          switch (wn) {
-            case 0: asm volatile(GSPMD_MAINLOOP_G1_W0 GSPMD_MAINLOOP_OPERANDS); break;
-            case 1: asm volatile(GSPMD_MAINLOOP_G1_W1 GSPMD_MAINLOOP_OPERANDS); break;
-            case 2: asm volatile(GSPMD_MAINLOOP_G1_W2 GSPMD_MAINLOOP_OPERANDS); break;
-            default: asm volatile(GSPMD_MAINLOOP_G1_W3 GSPMD_MAINLOOP_OPERANDS); break;
-          }
+#define GSPMD_RUN_MAINLOOP(L) \
+        if (wm == 0) { \
+          switch (wn) { \
+            case 0: asm volatile(GSPMD_MAINLOOP_L##L##_G0_W0 GSPMD_MAINLOOP_OPERANDS); break; \
+            case 1: asm volatile(GSPMD_MAINLOOP_L##L##_G0_W1 GSPMD_MAINLOOP_OPERANDS); break; \
+            case 2: asm volatile(GSPMD_MAINLOOP_L##L##_G0_W2 GSPMD_MAINLOOP_OPERANDS); break; \
+            default: asm volatile(GSPMD_MAINLOOP_L##L##_G0_W3 GSPMD_MAINLOOP_OPERANDS); break; \
+          } \
+        } else { \
+          switch (wn) { \
+            case 0: asm volatile(GSPMD_MAINLOOP_L##L##_G1_W0 GSPMD_MAINLOOP_OPERANDS); break; \
+            case 1: asm volatile(GSPMD_MAINLOOP_L##L##_G1_W1 GSPMD_MAINLOOP_OPERANDS); break; \
+            case 2: asm volatile(GSPMD_MAINLOOP_L##L##_G1_W2 GSPMD_MAINLOOP_OPERANDS); break; \
+            default: asm volatile(GSPMD_MAINLOOP_L##L##_G1_W3 GSPMD_MAINLOOP_OPERANDS); break; \
+          } \
         }
+        if constexpr (LAYOUT == 0) { GSPMD_RUN_MAINLOOP(0) }
+        else if constexpr (LAYOUT == 1) { GSPMD_RUN_MAINLOOP(1) }
+        else if constexpr (LAYOUT == 2) { GSPMD_RUN_MAINLOOP(2) }
+        else { GSPMD_RUN_MAINLOOP(3) }
       }
       GSPMD_WAIT_ALL();
       __syncthreads();
@@ -293,21 +327,27 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const Problem* _
   }
 }
 
-inline bool launch_dot_mfma(const Problem* tab, int n_prob, int tiles, int32_t out_dtype, hipStream_t stream) {
+template <typename TOut, int LAYOUT>
+inline bool launch_dot_mfma_as(const Problem* tab, int n_prob, int tiles, hipStream_t stream) {
   static bool attr_done = false;
   if (!attr_done) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&dot_mfma_kernel<float>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, kMfmaLds) != hipSuccess) return false;
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&dot_mfma_kernel<bf16_bits>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&dot_mfma_kernel<TOut, LAYOUT>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, kMfmaLds) != hipSuccess) return false;
     attr_done = true;
   }
   const dim3 grid(static_cast<unsigned>(tiles)), block(kMfmaThreads);
-  if (out_dtype == GSPMD_F32)
-    hipLaunchKernelGGL((dot_mfma_kernel<float>), grid, block, kMfmaLds, stream, tab, n_prob);
-  else
-    hipLaunchKernelGGL((dot_mfma_kernel<bf16_bits>), grid, block, kMfmaLds, stream, tab, n_prob);
+  hipLaunchKernelGGL((dot_mfma_kernel<TOut, LAYOUT>), grid, block, kMfmaLds, stream, tab, n_prob);
   return hipGetLastError() == hipSuccess;
+}
+
+inline bool launch_dot_mfma(const Problem* tab, int n_prob, int tiles, int32_t layout, int32_t out_dtype, hipStream_t stream) {
+  const bool f32 = out_dtype == GSPMD_F32;
+  switch (layout & 3) {
+    case 0: return f32 ? launch_dot_mfma_as<float, 0>(tab, n_prob, tiles, stream) : launch_dot_mfma_as<bf16_bits, 0>(tab, n_prob, tiles, stream);
+    case 1: return f32 ? launch_dot_mfma_as<float, 1>(tab, n_prob, tiles, stream) : launch_dot_mfma_as<bf16_bits, 1>(tab, n_prob, tiles, stream);
+    case 2: return f32 ? launch_dot_mfma_as<float, 2>(tab, n_prob, tiles, stream) : launch_dot_mfma_as<bf16_bits, 2>(tab, n_prob, tiles, stream);
+    default: return f32 ? launch_dot_mfma_as<float, 3>(tab, n_prob, tiles, stream) : launch_dot_mfma_as<bf16_bits, 3>(tab, n_prob, tiles, stream);
+  }
 }
 
 }  // namespace gspmd

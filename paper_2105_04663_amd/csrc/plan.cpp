@@ -230,7 +230,7 @@ int32_t plan_partition(const gspmd_mesh* mesh, const DotRoles& r,
                        const gspmd_shard_buf* rhs, const gspmd_sharding* rhs_sh,
                        const gspmd_shard_buf* out, const gspmd_sharding* out_sh,
                        int64_t pid, const int64_t* lhs_fill, void* c_override,
-                       std::vector<Problem>* problems, int64_t* out_static_elems) {
+                       std::vector<Problem>* problems, int64_t* out_static_elems, int32_t* layout) {
   Bounds lb, rb, ob;
   int32_t st;
   if ((st = shard_bounds(mesh, lhs_sh, pid, &lb)) != GSPMD_OK) return st;
@@ -238,13 +238,18 @@ int32_t plan_partition(const gspmd_mesh* mesh, const DotRoles& r,
   if ((st = shard_bounds(mesh, out_sh, pid, &ob)) != GSPMD_OK) return st;
   const int nb = r.nb, nc = r.nc, lr = lhs_sh->rank, rr = rhs_sh->rank;
 
-  // Supported layout: batch dims leading and in order; lhs contracting dims trailing; rhs
-  // contracting dims right after batch, in the same order.
+  // Supported dimension orders: the last (contiguous) dimension of each operand is its innermost
+  // contracting dimension (K contiguous) or its innermost non-contracting dimension (K-major),
+  // and the contracting dimensions nest alike in both operands (checked on the strides below).
+  // The forward einsums are lhs K-contiguous x rhs K-major; a weight gradient (tokens contract)
+  // is K-major x K-major, an input gradient K-contiguous x K-contiguous.
   if (nc == 0) return GSPMD_ERR_UNSUPPORTED;
-  for (int i = 0; i < nb; ++i)
-    if (r.lhs_batch[i] != i || r.rhs_batch[i] != i) return GSPMD_ERR_UNSUPPORTED;
-  for (int i = 0; i < nc; ++i)
-    if (r.lhs_contract[i] != lr - nc + i || r.rhs_contract[i] != nb + i) return GSPMD_ERR_UNSUPPORTED;
+  const bool a_kc = r.lhs_contract[nc - 1] == lr - 1;
+  const bool a_km = r.nlf > 0 && r.lhs_free[r.nlf - 1] == lr - 1;
+  const bool b_kc = r.rhs_contract[nc - 1] == rr - 1;
+  const bool b_km = r.nrf > 0 && r.rhs_free[r.nrf - 1] == rr - 1;
+  if (!(a_kc || a_km) || !(b_kc || b_km)) return GSPMD_ERR_UNSUPPORTED;   // a batch dimension is the contiguous one
+  if (layout) *layout = (a_km ? GSPMD_LAYOUT_LHS_K_MAJOR : 0) | (b_kc ? GSPMD_LAYOUT_RHS_K_CONTIGUOUS : 0);
 
   int64_t ls[kMaxRank], rs[kMaxRank], cs[kMaxRank];
   if ((st = shard_strides(lb, lhs->row_stride, ls)) != GSPMD_OK) return st;
@@ -273,11 +278,10 @@ int32_t plan_partition(const gspmd_mesh* mesh, const DotRoles& r,
   const Layout lm = flatten_free(r.lhs_free, r.nlf, nb, lb, ls, ob, cs);
   const Layout ln = flatten_free(r.rhs_free, r.nrf, nb + r.nlf, rb, rs, ob, cs);
 
-  // leading dimensions of the flattened views
-  const int64_t lda = r.nlf ? ls[r.lhs_free[r.nlf - 1]] : Ks;
-  const int64_t ldb = rs[r.rhs_contract[nc - 1]];
+  // leading dimensions of the flattened views: the stride of whichever index is not contiguous
+  const int64_t lda = a_km ? ls[r.lhs_contract[nc - 1]] : (r.nlf ? ls[r.lhs_free[r.nlf - 1]] : Ks);
+  const int64_t ldb = b_km ? rs[r.rhs_contract[nc - 1]] : (r.nrf ? rs[r.rhs_free[r.nrf - 1]] : Ks);
   const int64_t ldc = r.nlf ? cs[nb + r.nlf - 1] : ln.inner_static;
-  if (r.nrf && rs[r.rhs_free[r.nrf - 1]] != 1) return GSPMD_ERR_UNSUPPORTED;
   const int64_t lim = INT32_MAX;
   if (lm.inner_static > lim || ln.inner_static > lim || Ks > lim || lda > lim || ldb > lim || ldc > lim)
     return GSPMD_ERR_UNSUPPORTED;
@@ -289,10 +293,11 @@ int32_t plan_partition(const gspmd_mesh* mesh, const DotRoles& r,
   int64_t extent[3 * kMaxRank], valid[3 * kMaxRank], sa[3 * kMaxRank], sb[3 * kMaxRank], sc[3 * kMaxRank];
   int64_t goff[3 * kMaxRank], gsize[3 * kMaxRank];   // global offset/size of batch dims (for fill lookup)
   for (int i = 0; i < nb; ++i) {
-    extent[n_loop] = lb.shard[i]; valid[n_loop] = lb.valid[i];
-    if (lb.valid[i] != rb.valid[i] || lb.valid[i] != ob.valid[i]) return GSPMD_ERR_NEEDS_RESHARD;
-    sa[n_loop] = ls[i]; sb[n_loop] = rs[i]; sc[n_loop] = cs[i];
-    goff[n_loop] = lb.offset[i]; gsize[n_loop] = lhs_sh->global_shape[i];
+    const int ld = r.lhs_batch[i], rd = r.rhs_batch[i];
+    extent[n_loop] = lb.shard[ld]; valid[n_loop] = lb.valid[ld];
+    if (lb.valid[ld] != rb.valid[rd] || lb.valid[ld] != ob.valid[i]) return GSPMD_ERR_NEEDS_RESHARD;
+    sa[n_loop] = ls[ld]; sb[n_loop] = rs[rd]; sc[n_loop] = cs[i];
+    goff[n_loop] = lb.offset[ld]; gsize[n_loop] = lhs_sh->global_shape[ld];
     ++n_loop;
   }
   for (int i = 0; i < lm.n_outer; ++i) {

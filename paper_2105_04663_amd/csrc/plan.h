@@ -12,10 +12,12 @@ namespace gspmd {
 
 // One strided GEMM the device kernels run:  C[m,n] = sum_k A[m,k] * B[k,n]  for
 // m < Mv, n < Nv, k < Kv; C is written as 0 for the rest of [Ms, Ns].
-// 64 bytes; the device reads an array of these.
+// 64 bytes; the device reads an array of these.  Which index of A and of B is the contiguous
+// one is the same for every problem of a launch (it follows from the Dot's dimension order)
+// and travels beside the table as a mask of GSPMD_LAYOUT_* bits.
 struct Problem {
-  const void* A;      // element (m,k) at A + m*lda + k
-  const void* B;      // element (k,n) at B + k*ldb + n
+  const void* A;      // element (m,k) at A + m*lda + k;  lhs K-major: A + k*lda + m
+  const void* B;      // element (k,n) at B + k*ldb + n;  rhs K-contiguous: B + n*ldb + k
   void* C;            // element (m,n) at C + m*ldc + n
   int32_t Mv, Nv, Kv; // valid extents (what is read / computed)
   int32_t Ms, Ns;     // static extents of the output block (zero-filled beyond valid)
@@ -63,7 +65,7 @@ int32_t plan_partition(const gspmd_mesh* mesh, const DotRoles& roles,
                        const gspmd_shard_buf* rhs, const gspmd_sharding* rhs_sh,
                        const gspmd_shard_buf* out, const gspmd_sharding* out_sh,
                        int64_t pid, const int64_t* lhs_fill, void* c_override,
-                       std::vector<Problem>* problems, int64_t* out_static_elems);
+                       std::vector<Problem>* problems, int64_t* out_static_elems, int32_t* layout);
 
 // Number of problems plan_partition would emit and the static out shard elements.
 int32_t count_partition(const gspmd_mesh* mesh, const DotRoles& roles,

@@ -127,3 +127,30 @@ def test_second_moe_einsum_full_size():
         rows = sample_rows(f, [256, 512], seed=80 + e, extra=4)
         ref = od.dot_general(wl.bf16_bits_to_f64(lhs[e, rows]), wl.bf16_bits_to_f64(rhs[e]), (), (), (1,), (0,))
         check(to_f64(out[e, torch.from_numpy(rows).cuda()].contiguous()), ref, f"ECH,EHM->ECM expert {e}")
+
+
+def test_weight_gradient_full_size():
+    # BSM,BSH->MH: the 16384 tokens contract; both operands K-major
+    w = wl.ffn_wgrad()
+    lhs, rhs = w.draw_lhs(), w.draw_rhs()
+    st = Staged(w, lhs, rhs, row_align=8)
+    st.run_grouped()
+    torch.cuda.synchronize()
+    m_idx = sample_rows(8192, [256, 4096, 7936], seed=9, extra=6)
+    ref = od.dot_general(wl.bf16_bits_to_f64(lhs[:, :, m_idx]), wl.bf16_bits_to_f64(rhs), (), (), (0, 1), (0, 1))
+    got = to_f64(out_tensor(st, 0)[torch.from_numpy(m_idx).cuda()].contiguous())
+    check(got, ref, "BSM,BSH->MH")
+
+
+def test_input_gradient_full_size():
+    # BSH,MH->BSM: both operands K-contiguous
+    w = wl.ffn_dgrad()
+    lhs, rhs = w.draw_lhs(), w.draw_rhs()
+    st = Staged(w, lhs, rhs, row_align=8)
+    st.run_grouped()
+    torch.cuda.synchronize()
+    s_idx = sample_rows(2048, [256, 1024, 1792], seed=10, extra=6)
+    ref = od.dot_general(wl.bf16_bits_to_f64(lhs[:, s_idx, :]), wl.bf16_bits_to_f64(rhs), (), (), (2,), (1,))
+    out = out_tensor(st, 0).view(8, 2048, 8192)
+    got = to_f64(out[:, torch.from_numpy(s_idx).cuda(), :].contiguous())
+    check(got, ref, "BSH,MH->BSM")

@@ -265,6 +265,65 @@ def test_two_contracting_dims_and_batch_fp32():
         check(st.out_shard(pid), ref, fro_tol=1e-5)
 
 
+# --------------------------------------------------------------------------- backward-pass layouts
+LAYOUTS = {  # name -> (lhs shape from (M,K), rhs shape from (K,N), lhs contracting dim, rhs contracting dim)
+    "tn": (lambda M, K: (K, M), lambda K, N: (K, N), 0, 0),     # weight gradient: both operands K-major
+    "nt": (lambda M, K: (M, K), lambda K, N: (N, K), 1, 1),     # input gradient: both operands K-contiguous
+    "tt": (lambda M, K: (K, M), lambda K, N: (N, K), 0, 1),
+}
+
+
+def _layout_workload(layout, M, K, N, mesh_shape=(1,), lmap=(-1, -1), rmap=(-1, -1), omap=(-1, -1), out_dtype="bf16"):
+    ls, rs, lc, rc = LAYOUTS[layout]
+    return _generic(ls(M, K), rs(K, N), (), (), (lc,), (rc,), mesh_shape, lmap, rmap, omap, out_dtype=out_dtype)
+
+
+@pytest.mark.parametrize("layout", ["tn", "nt", "tt"])
+@pytest.mark.parametrize("M,K,N", [(600, 200, 520), (257, 64, 255), (1, 8, 1), (513, 72, 1030), (40, 4104, 24),
+                                   (260, 33, 264), (260, 95, 264), (260, 127, 264), (260, 321, 264)])
+def test_transposed_layouts_ragged(layout, M, K, N):
+    w = _layout_workload(layout, M, K, N)
+    lhs, rhs = wl.draw_normal_bf16(1, w.lhs_shape), wl.draw_normal_bf16(2, w.rhs_shape, 0.05)
+    st = Staged(w, lhs, rhs, row_align=8)
+    st.run_local(0)
+    compare_all_shards(st, w, oracle_global(w, lhs, rhs))
+
+
+@pytest.mark.parametrize("layout", ["tn", "nt", "tt"])
+@pytest.mark.parametrize("row_align", [8, 0])
+def test_transposed_layouts_integer_exact_poisoned_uneven_mesh(layout, row_align):
+    # M and N uneven over a 2 x 3 mesh with permuted ids, K with a tail; pads hold NaN; integers make fp32 exact
+    ids = np.random.default_rng(11).permutation(6).tolist()
+    ls, rs, lc, rc = LAYOUTS[layout]
+    lmap = (0, -1) if lc == 1 else (-1, 0)
+    rmap = (-1, 1) if rc == 0 else (1, -1)
+    w = _layout_workload(layout, 601, 203, 530, (2, 3), lmap, rmap, (0, 1), out_dtype="f32")
+    w.device_ids = tuple(ids)
+    lhs, rhs = wl.draw_small_int_bf16(5, w.lhs_shape), wl.draw_small_int_bf16(6, w.rhs_shape)
+    st = Staged(w, lhs, rhs, row_align=row_align, out_dtype="f32")
+    assert g.classify_dot(st.mesh, st.dims, st.lhs_sh, st.rhs_sh, st.out_sh) == (g.AXIS_LHS_FREE, g.AXIS_RHS_FREE)
+    st.run_grouped()
+    compare_all_shards(st, w, oracle_global(w, lhs, rhs), exact=True)
+
+
+def test_backward_einsums_small():
+    # weight gradient BSM,BSH->MH: B split 3 ways over X (contracting, uneven 5/3 -> 2,2,1), H over Y
+    w = wl.ffn_wgrad(B=5, S=70, M=264, H=520, X=3, Y=2)
+    lhs, rhs = wl.draw_normal_bf16(1, w.lhs_shape), wl.draw_normal_bf16(2, w.rhs_shape, 0.05)
+    st = Staged(w, lhs, rhs, row_align=8)
+    assert g.classify_dot(st.mesh, st.dims, st.lhs_sh, st.rhs_sh, st.out_sh) == (g.AXIS_CONTRACTING, g.AXIS_RHS_FREE)
+    assert all(d["layout"] == g.LAYOUT_LHS_K_MAJOR for d in g.plan_dot(st.mesh, st.dims, st.lhs_sh, st.rhs_sh, st.out_sh, 0, 264, 264, 264))
+    st.run_grouped()
+    compare_all_shards(st, w, oracle_global(w, lhs, rhs))
+    # input gradient BSH,MH->BSM: B over X (lhs non-contracting), H over Y (contracting, uneven 1000/3)
+    w = wl.ffn_dgrad(B=3, S=70, H=1000, M=264, X=2, Y=3)
+    lhs, rhs = wl.draw_normal_bf16(1, w.lhs_shape), wl.draw_normal_bf16(2, w.rhs_shape, 0.05)
+    st = Staged(w, lhs, rhs, row_align=8)
+    assert g.classify_dot(st.mesh, st.dims, st.lhs_sh, st.rhs_sh, st.out_sh) == (g.AXIS_LHS_FREE, g.AXIS_CONTRACTING)
+    st.run_grouped()
+    compare_all_shards(st, w, oracle_global(w, lhs, rhs))
+
+
 def test_second_layer_einsums_small():
     # BSH,HM->BSM with H split over 4 partitions (uneven: 1000/4 = 250, rows padded to 256) and bf16 output of the sum
     w = wl.ffn_second(B=3, S=70, H=1000, M=264, Y=4)

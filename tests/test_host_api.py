@@ -158,9 +158,9 @@ def test_device_calls_validate_before_touching_the_gpu():
         g.local_dot(MESH, MM, g.ShardBuf(256, g.BF16, 16), S((64, 32), (0, -1)), g.ShardBuf(256, g.BF16, 0), S((32, 48), (-1, 1)),
                     g.ShardBuf(256, g.BF16, 0), S((64, 48), (0, 1)), 0)
     assert e.value.status == 10
-    with pytest.raises(g.GspmdError) as e:   # unsupported layout: lhs contracting dim leading
-        g.local_dot(MESH, g.DotDims((), (), (0,), (0,)), g.ShardBuf(256, g.BF16, 0), S((32, 64), (-1, 0)), g.ShardBuf(256, g.BF16, 0),
-                    S((32, 48), (-1, 1)), g.ShardBuf(256, g.BF16, 0), S((64, 48), (0, 1)), 0)
+    with pytest.raises(g.GspmdError) as e:   # unsupported dimension order: a batch dim is the lhs's contiguous one
+        g.local_dot(MESH, g.DotDims((2,), (0,), (1,), (1,)), g.ShardBuf(256, g.BF16, 0), S((64, 32, 4), (0, -1, -1)),
+                    g.ShardBuf(256, g.BF16, 0), S((4, 32, 48), (-1, -1, 1)), g.ShardBuf(256, g.BF16, 0), S((4, 64, 48), (-1, 0, 1)), 0)
     assert e.value.status == 7
     with pytest.raises(g.GspmdError) as e:
         g.reduce_partials([], 10, 256, g.F32)

@@ -36,8 +36,10 @@ def make_shard(glob, mesh_shape, ids, mapping, pid, row_stride, poison=np.nan):
 def run_plan(descs, a, b, c):
     for d in descs:
         M, N, K = d["m_valid"], d["n_valid"], d["k_valid"]
-        A = np.lib.stride_tricks.as_strided(a[d["a_offset"]:], shape=(M, K), strides=(8 * d["lda"], 8)) if M and K else np.zeros((M, K))
-        B = np.lib.stride_tricks.as_strided(b[d["b_offset"]:], shape=(K, N), strides=(8 * d["ldb"], 8)) if N and K else np.zeros((K, N))
+        a_str = (8, 8 * d["lda"]) if d["layout"] & g.LAYOUT_LHS_K_MAJOR else (8 * d["lda"], 8)
+        b_str = (8, 8 * d["ldb"]) if d["layout"] & g.LAYOUT_RHS_K_CONTIGUOUS else (8 * d["ldb"], 8)
+        A = np.lib.stride_tricks.as_strided(a[d["a_offset"]:], shape=(M, K), strides=a_str) if M and K else np.zeros((M, K))
+        B = np.lib.stride_tricks.as_strided(b[d["b_offset"]:], shape=(K, N), strides=b_str) if N and K else np.zeros((K, N))
         C = np.lib.stride_tricks.as_strided(c[d["c_offset"]:], shape=(d["m_static"], d["n_static"]), strides=(8 * d["ldc"], 8))
         C[:, :] = 0.0
         if M and N and K:
@@ -45,50 +47,61 @@ def run_plan(descs, a, b, c):
             C[:M, :N] = A @ B
 
 
+ORDERS = {  # dimension order of (lhs, rhs) by role: b batch, l/r non-contracting, c contracting
+    "nn": ("blc", "bcr"),   # forward einsums
+    "tn": ("bcl", "bcr"),   # weight gradient: the token dims contract and lead in both operands
+    "nt": ("blc", "brc"),   # input gradient: contracting dims trail in both operands
+    "tt": ("bcl", "brc"),
+}
+
+
 @st.composite
 def sharded_dot(draw):
     nb, nlf, nc, nrf = draw(st.integers(0, 2)), draw(st.integers(1, 2)), draw(st.integers(1, 2)), draw(st.integers(1, 2))
     size = lambda: draw(st.integers(1, 7))
-    bsz, lfsz, csz, rfsz = [size() for _ in range(nb)], [size() for _ in range(nlf)], [size() for _ in range(nc)], [size() for _ in range(nrf)]
-    lhs_shape, rhs_shape, out_shape = bsz + lfsz + csz, bsz + csz + rfsz, bsz + lfsz + rfsz
+    sizes = {"b": [size() for _ in range(nb)], "l": [size() for _ in range(nlf)], "c": [size() for _ in range(nc)],
+             "r": [size() for _ in range(nrf)]}
+    order = draw(st.sampled_from(["nn", "nn", "tn", "nt", "tt", "random"]))
+    if order == "random":
+        lhs_roles = draw(st.permutations([(k, i) for k in "blc" for i in range(len(sizes[k]))]))
+        rhs_roles = draw(st.permutations([(k, i) for k in "bcr" for i in range(len(sizes[k]))]))
+    else:
+        lhs_roles = [(k, i) for k in ORDERS[order][0] for i in range(len(sizes[k]))]
+        rhs_roles = [(k, i) for k in ORDERS[order][1] for i in range(len(sizes[k]))]
+    # output order: batch pairs as listed, then the non-contracting dims of each operand in operand order
+    out_roles = [("b", i) for i in range(nb)] + [x for x in lhs_roles if x[0] == "l"] + [x for x in rhs_roles if x[0] == "r"]
     mrank = draw(st.integers(1, 3))
     mshape = [draw(st.integers(1, 3)) for _ in range(mrank)]
     P = int(np.prod(mshape))
     ids = draw(st.permutations(list(range(P))))
-    lmap, rmap, omap = [-1] * len(lhs_shape), [-1] * len(rhs_shape), [-1] * len(out_shape)
     # each mesh dim carries one of the communication-free patterns on a dim not yet split
-    free = {"b": list(range(nb)), "l": list(range(nlf)), "c": list(range(nc)), "r": list(range(nrf))}
+    axis_of = {}
+    free = {k: list(range(len(sizes[k]))) for k in "blcr"}
     for axis in range(mrank):
         kinds = [k for k in "blcr" if free[k]] + ["u"]
         kind = draw(st.sampled_from(kinds))
-        if kind == "u":
-            continue
-        i = free[kind].pop(draw(st.integers(0, len(free[kind]) - 1)))
-        if kind == "b":
-            lmap[i] = rmap[i] = omap[i] = axis
-        elif kind == "l":
-            lmap[nb + i] = omap[nb + i] = axis
-        elif kind == "r":
-            rmap[nb + nc + i] = omap[nb + nlf + i] = axis
-        else:
-            lmap[nb + nlf + i] = rmap[nb + i] = axis
+        if kind != "u":
+            axis_of[(kind, free[kind].pop(draw(st.integers(0, len(free[kind]) - 1))))] = axis
+    shape = lambda roles: tuple(sizes[k][i] for k, i in roles)
+    lmap = tuple(axis_of.get(x, -1) for x in lhs_roles)
+    rmap = tuple(axis_of.get(x, -1) for x in rhs_roles)
+    omap = tuple(-1 if x[0] == "c" else axis_of.get(x, -1) for x in out_roles)
+    where = lambda roles, k: tuple(roles.index((k, i)) for i in range(len(sizes[k])))
+    dims = (where(lhs_roles, "b"), where(rhs_roles, "b"), where(lhs_roles, "c"), where(rhs_roles, "c"))
     strides = [draw(st.sampled_from([0, 1, 3])) for _ in range(3)]     # extra row padding per tensor
-    return dict(lhs_shape=tuple(lhs_shape), rhs_shape=tuple(rhs_shape), out_shape=tuple(out_shape), nb=nb, nlf=nlf, nc=nc, nrf=nrf,
-                mshape=tuple(mshape), ids=tuple(ids), lmap=tuple(lmap), rmap=tuple(rmap), omap=tuple(omap), pad=strides,
+    return dict(lhs_shape=shape(lhs_roles), rhs_shape=shape(rhs_roles), out_shape=shape(out_roles), nc=nc, order=order, dims=dims,
+                mshape=tuple(mshape), ids=tuple(ids), lmap=lmap, rmap=rmap, omap=omap, pad=strides,
                 seed=draw(st.integers(0, 1 << 30)))
 
 
-@settings(max_examples=250, deadline=None, suppress_health_check=[HealthCheck.too_slow])
+@settings(max_examples=400, deadline=None, suppress_health_check=[HealthCheck.too_slow])
 @given(sharded_dot())
 def test_lowered_problems_reproduce_the_oracle(c):
     rng = np.random.default_rng(c["seed"])
     lhs = rng.integers(-4, 5, size=c["lhs_shape"]).astype(np.float64)
     rhs = rng.integers(-4, 5, size=c["rhs_shape"]).astype(np.float64)
-    nb, nlf, nc = c["nb"], c["nlf"], c["nc"]
-    lb, rb = tuple(range(nb)), tuple(range(nb))
-    lc, rc = tuple(range(nb + nlf, nb + nlf + nc)), tuple(range(nb, nb + nc))
-    dims = (lb, rb, lc, rc)
-    mesh, gd = g.Mesh(c["mshape"], c["ids"]), g.DotDims(lb, rb, lc, rc)
+    dims, nc = c["dims"], c["nc"]
+    mesh, gd = g.Mesh(c["mshape"], c["ids"]), g.DotDims(*dims)
     lsh, rsh, osh = g.Sharding(c["lhs_shape"], c["lmap"]), g.Sharding(c["rhs_shape"], c["rmap"]), g.Sharding(c["out_shape"], c["omap"])
     contracting = g.AXIS_CONTRACTING in g.classify_dot(mesh, gd, lsh, rsh, osh)
     out_global = od.dot_general(lhs, rhs, *dims)
@@ -100,9 +113,14 @@ def test_lowered_problems_reproduce_the_oracle(c):
         try:
             descs = g.plan_dot(mesh, gd, lsh, rsh, osh, pid, lrs, rrs, ors)
         except g.GspmdError as e:
-            # the only refusal allowed here: several contracting dims that padding or row padding keeps from flattening
-            assert e.status == 7 and nc > 1
+            # refusals allowed here: several contracting dims that padding or row padding keeps from flattening, and
+            # (random orders only) a batch dim last or contracting dims that nest differently in the two operands
+            assert e.status == 7 and (nc > 1 or c["order"] == "random")
             continue
+        want_layout = {"nn": 0, "tn": g.LAYOUT_LHS_K_MAJOR, "nt": g.LAYOUT_RHS_K_CONTIGUOUS,
+                       "tt": g.LAYOUT_LHS_K_MAJOR | g.LAYOUT_RHS_K_CONTIGUOUS}.get(c["order"])
+        if want_layout is not None:
+            assert all(d["layout"] == want_layout for d in descs)
         a, _, _, _ = make_shard(lhs, c["mshape"], c["ids"], c["lmap"], pid, lrs)
         b, _, _, _ = make_shard(rhs, c["mshape"], c["ids"], c["rmap"], pid, rrs)
         cbuf, cview, cshard, cvalid = make_shard(np.full(c["out_shape"], 7.0), c["mshape"], c["ids"], c["omap"], pid, ors, poison=7.0)

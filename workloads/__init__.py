@@ -256,5 +256,29 @@ def moe_second(E: int = 4, C: int = 1024, H: int = 32768, M: int = 8192) -> DotW
         fill_range=(C // 2, C), einsum="ECH,EHM->ECM")
 
 
+def ffn_wgrad(B: int = 8, S: int = 2048, M: int = 8192, H: int = 8192, X: int = 1, Y: int = 1) -> DotWorkload:
+    """Weight gradient of the first feed-forward einsum, BSM,BSH->MH: the token dims contract, so both operands are
+    K-major.  With B split over X partitions (data parallelism) every partition holds a partial gradient that the
+    AllReduce / ReduceScatter over X sums (Section 3.2's backward pass); H stays split over Y.  X = Y = 1 is one
+    device's share of the 2-D mesh."""
+    return DotWorkload(
+        name="ffn_wgrad_bsm_bsh", cfg=9, dtype="bf16", out_dtype="bf16",
+        lhs_shape=(B, S, M), rhs_shape=(B, S, H),
+        lhs_batch=(), rhs_batch=(), lhs_contract=(0, 1), rhs_contract=(0, 1),
+        mesh_shape=(X, Y), device_ids=_ids(X * Y),
+        lhs_map=(0, -1, -1), rhs_map=(0, -1, 1), out_map=(-1, 1), rhs_sigma=1.0, einsum="BSM,BSH->MH")
+
+
+def ffn_dgrad(B: int = 8, S: int = 2048, H: int = 8192, M: int = 8192, X: int = 1, Y: int = 1) -> DotWorkload:
+    """Input gradient of the first feed-forward einsum, BSH,MH->BSM: H contracts and is the last dimension of both
+    operands (both K-contiguous).  B split over X (lhs non-contracting), H over Y (contracting: partial sums)."""
+    return DotWorkload(
+        name="ffn_dgrad_bsh_mh", cfg=10, dtype="bf16", out_dtype="bf16",
+        lhs_shape=(B, S, H), rhs_shape=(M, H),
+        lhs_batch=(), rhs_batch=(), lhs_contract=(2,), rhs_contract=(1,),
+        mesh_shape=(X, Y), device_ids=_ids(X * Y),
+        lhs_map=(0, -1, 1), rhs_map=(-1, 1), out_map=(0, -1, -1), einsum="BSH,MH->BSM")
+
+
 def all_configs() -> List[DotWorkload]:
     return [tiny_1d(), ffn(), ksplit(), moe(), mesh2d()]
