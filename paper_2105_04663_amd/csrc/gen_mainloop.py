@@ -5,7 +5,7 @@ Run `python gen_mainloop.py > mainloop_asm.h` after changing the schedule; the g
 the build does not run this script.
 
 Shape of the loop.  K advances in steps of 64 = two LDS tiles of 32.  LDS has five 32 KiB stages (tile t lives in
-stage t % 5: A part [256 m][32 k], B part [32 k][256 n]).  The workgroup's two wave groups (waves 0-3 and 4-7; wave
+stage t % 5: A part and B part of 16 KiB each, formats below).  The workgroup's two wave groups (waves 0-3 and 4-7; wave
 w and w+4 share a SIMD) alternate, one phase apart and separated by s_barrier, between
   * a read phase: all fragments of one K step, 32 LDS reads (16 ds_read_b128 for A, 16 ds_read_b64_tr_b16 for B)
     into 96 VGPRs, and
@@ -21,12 +21,20 @@ tile 2u+4 during the MFMA phase of step u, group 1 tile 2u+5.  With five stages 
 phase (>= 1024 cycles) plus the slack of a read phase to land; s_waitcnt vmcnt sits right before the barrier that
 publishes the tile.
 
-Operand layouts.  Each operand's LDS tile keeps the operand's own memory order, so there are two tile formats:
-K-contiguous ([256 rows][32 k], fragment = one ds_read_b128) and K-major ([32 k][256 columns], fragment = two
-ds_read_b64_tr_b16, block b of 16 columns at address ^ (b << 5)).  The forward einsums have a K-contiguous lhs and a
-K-major rhs; a weight gradient has both K-major, an input gradient both K-contiguous.  One set of macros is written
-per combination (GSPMD_MAINLOOP_L<layout>_..., layout bit 0 = lhs K-major, bit 1 = rhs K-contiguous); only the read
-phase differs (32, 48, 24 or 40 LDS reads into the same 96 fragment registers).
+Operand layouts.  Each operand's LDS tile keeps the operand's own memory order, so there are two tile formats.
+K-major (rows of 256 m resp. n): the part of tile t is [32 k][256 columns]; a fragment is two ds_read_b64_tr_b16,
+block b of 16 columns at address ^ (b << 5).
+K-contiguous: the two parts of K step u (tiles 2u and 2u+1) hold the operand's 256 rows as two halves of
+[128 rows][64 k] -- rows 0-127 in tile 2u's part, rows 128-255 in tile 2u+1's -- so that a row is a whole 128-byte
+line of global memory (a [256][32] part would fetch half lines and cost the texture-address unit twice the lookups per
+load instruction).  A wave reads all its K-contiguous fragments of the step from ONE part (the half its rows are in;
+stage offset in s55 for the lhs, s56 for the rhs, advancing two stages per step): one ds_read_b128 per fragment, the
+second 32 k at address ^ 64.  Who loads what, and when a stage is free again, is the same as for K-major parts: the
+part of tile t is loaded with tile t, by group t & 1, and stage t % 5 is last read in the read phase of group 1.
+The forward einsums have a K-contiguous lhs and a K-major rhs; a weight gradient has both K-major, an input gradient
+both K-contiguous.  One set of macros is written per combination (GSPMD_MAINLOOP_L<layout>_..., layout bit 0 = lhs
+K-major, bit 1 = rhs K-contiguous); only the read phase differs (32, 48, 24 or 40 LDS reads into the same 96 fragment
+registers).
 
 Register plan per wave: v[0:127] accumulators acc(bm, bn) = v[4*(4*bm+bn) ..+3] (bm = 16-row block 0..7 of the
 wave's 128 rows, bn = 16-column block 0..3 of its 64 columns); fragments of tile q (0/1) of the K step:
@@ -36,7 +44,7 @@ takes its address when it issues, so the two registers alternate).
 SGPRs: s[40:41]/s[42:43] pointers to the next A/B tile this group loads, s44 this wave's LDS write base (stage 0),
 s45 K steps left, s46 pointer advances left (the pointers stop at the last full tile: loads issued past it re-read
 that tile into a stage nobody reads any more), s47/s54 B/A pointer step in bytes (two tiles), s52 write-stage offset,
-s53 read-stage offset, s48-s51 temporaries.
+s53 read-stage offset (K-major parts), s55/s56 read-stage offsets of a K-contiguous lhs/rhs, s48-s51 temporaries.
 """
 import sys
 
@@ -69,10 +77,18 @@ def xor_const(dst, c, src):
     return f"v_xor_b32 {dst}, {c if c <= 64 else hex(c)}, {src}"
 
 
-def read_addrs(layout):
-    out = ["v_add_u32 v224, s53, %[ard]", "v_add_u32 v225, s53, %[brd]"]
-    if not layout & 2:  # K-major rhs: one address per 16-column block
+def read_addrs(layout, q):
+    """Address registers for the reads of tile q (0/1) of the step."""
+    out = []
+    if layout & 1:          # K-major lhs: stage of tile 2u+q
+        out.append("v_add_u32 v224, s53, %[ard]")
+    elif q == 0:            # K-contiguous lhs: this wave's half, both tiles' k from one part
+        out += ["v_add_u32 v224, s55, %[ard]", xor_const("v229", 64, "v224")]
+    if not layout & 2:      # K-major rhs: one address per 16-column block
+        out.append("v_add_u32 v225, s53, %[brd]")
         out += [xor_const(f"v{225 + bn}", bn << 5, "v225") for bn in range(1, 4)]
+    elif q == 0:
+        out += ["v_add_u32 v225, s56, %[brd]", xor_const("v226", 64, "v225")]
     return out
 
 
@@ -86,10 +102,10 @@ def ds_reads(q, layout):
             for rd in range(2):
                 out.append(f"ds_read_b64_tr_b16 {fa(q, bm, rd)}, {reg} offset:{rd * 2048}")
         else:
-            out.append(f"ds_read_b128 {fa(q, bm)}, v224 offset:{bm * 1024}")
+            out.append(f"ds_read_b128 {fa(q, bm)}, {'v229' if q else 'v224'} offset:{bm * 2048}")
     for bn in range(4):
         if layout & 2:
-            out.append(f"ds_read_b128 {fb(q, bn)}, v225 offset:{bn * 1024}")
+            out.append(f"ds_read_b128 {fb(q, bn)}, {'v226' if q else 'v225'} offset:{bn * 2048}")
         else:
             for rd in range(2):
                 out.append(f"ds_read_b64_tr_b16 {fb(q, bn, rd)}, v{225 + bn} offset:{rd * 2048}")
@@ -101,8 +117,13 @@ def step_stage(reg, n):
 
 
 def mem_phase(layout):
-    return (read_addrs(layout) + ds_reads(0, layout) + step_stage("s53", 1)
-            + read_addrs(layout) + ds_reads(1, layout) + step_stage("s53", 1))
+    out = (read_addrs(layout, 0) + ds_reads(0, layout) + step_stage("s53", 1)
+           + read_addrs(layout, 1) + ds_reads(1, layout) + step_stage("s53", 1))
+    if not layout & 1:
+        out += step_stage("s55", 2)
+    if layout & 2:
+        out += step_stage("s56", 2)
+    return out
 
 
 def load(j):

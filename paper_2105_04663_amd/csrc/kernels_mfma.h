@@ -6,8 +6,10 @@
 //
 // Workgroup tile 256 x 256, 8 wavefronts (2 along m x 4 along n), each owning a 128 x 64 block as 8 x 4
 // v_mfma_f32_16x16x32_bf16 tiles (128 accumulator registers per lane), one workgroup per CU.
-// LDS (all 160 KiB) holds five stages of a 32-wide K tile: A part [256 m][32 k] and B part [32 k][256 n], both in
-// the operands' own memory order and filled by direct global->LDS loads (no register staging, no ds_write);
+// LDS (all 160 KiB) holds five stages of a 32-wide K tile, an A part and a B part of 16 KiB each, both in
+// the operands' own memory order and filled by direct global->LDS loads (no register staging, no ds_write):
+// the B part is [32 k][256 n]; the A parts of the two tiles of a 64-wide K step hold rows 0-127 and rows 128-255 of
+// the tile as [128 m][64 k], so that every row is a whole 128-byte line of global memory.
 // 16-byte chunks are XOR-swizzled inside a row -- on the global-address side, since a direct load writes lane i's
 // 16 bytes at LDS base + 16*i -- so that fragment reads are bank-conflict free.  The B fragment needs k along the
 // lane's registers while memory has n contiguous: it is read with the LDS transpose read (ds_read_b64_tr_b16),
@@ -86,7 +88,27 @@ __device__ __forceinline__ int logical_tile(int b, int total) {
 
 constexpr int kBandRows = 8;
 
-// Per-lane byte offset, relative to the tile's base, of load instruction q (0..15) of a K-contiguous operand tile
+__device__ __forceinline__ int swz_h(int row) { return (row >> 1) & 7; }
+
+// Main loop, K-contiguous operand: part `half` (0/1) of a 64-wide K step is [128 rows][64 k] with 128-byte rows.
+// Per-lane byte offset, relative to the address of (first row of the 256-row tile, first k of the step), of load
+// instruction q (0..15; rows 8q..8q+7 of the half, 8 lanes per row).  Rows past the valid extent reuse the last
+// valid row (their results are never stored).
+__device__ __forceinline__ int kc_half_load_offset(int q, int lane, int half, int r0, int rows_valid, int ld) {
+  const int r = q * 8 + (lane >> 3);
+  const int c = (lane & 7) ^ swz_h(r);
+  const int rr = min(r0 + half * 128 + r, rows_valid - 1) - r0;
+  return (rr * ld + c * 8) * 2;
+}
+// LDS byte offset inside the part of a lane's first fragment (first 32 k of the step; the second at ^ 64) of the
+// 16-row block whose first row inside the half is `base`; block b at + b * 2048.
+__device__ __forceinline__ int kc_half_frag_offset(int base, int lane) {
+  const int row = base + (lane & 15);
+  return row * 128 + (((lane >> 4) ^ swz_h(row)) << 4);
+}
+
+// What is left of K after the main loop uses [256 rows][32 k] parts for a K-contiguous operand:
+// per-lane byte offset, relative to the tile's base, of load instruction q (0..15) of a K-contiguous operand tile
 // ([256 rows][32 k]: instruction q covers rows 16q..16q+15, 4 lanes per row).  Rows past the valid extent reuse the
 // last valid row (their results are never stored).
 __device__ __forceinline__ int kc_load_offset(int q, int lane, int r0, int rows_valid, int ld) {
@@ -149,24 +171,28 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const Problem* _
     const bf16_bits* __restrict__ Bbase = static_cast<const bf16_bits*>(P.B) + (BKC ? static_cast<int64_t>(n0) * P.ldb : static_cast<int64_t>(n0));
     const int64_t a_tile = AKM ? static_cast<int64_t>(kMfmaBK) * P.lda : kMfmaBK;
     const int64_t b_tile = BKC ? kMfmaBK : static_cast<int64_t>(kMfmaBK) * P.ldb;
-    const int nk32 = P.Kv / kMfmaBK;          // full 32-wide K tiles
     const int nk64 = P.Kv / (2 * kMfmaBK);    // full 64-wide K steps (the assembly loop)
+    const int nkt = 2 * nk64;                 // 32-wide tiles the assembly loop consumes
 
     // ---- tile loads.  A tile (32 KiB) is 32 wave-instructions of 1 KiB (16 per operand); the four waves of ONE
     // group load a whole tile, wave wn taking instructions 4*wn .. 4*wn+3 of each operand.
+    // Group wm loads the tiles of its own parity, hence the half wm of a K-contiguous operand.
     int a_off[4], b_off[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      a_off[j] = AKM ? km_load_offset(wn * 4 + j, lane, m0, P.Mv, P.lda) : kc_load_offset(wn * 4 + j, lane, m0, P.Mv, P.lda);
-      b_off[j] = BKC ? kc_load_offset(wn * 4 + j, lane, n0, P.Nv, P.ldb) : km_load_offset(wn * 4 + j, lane, n0, P.Nv, P.ldb);
+      a_off[j] = AKM ? km_load_offset(wn * 4 + j, lane, m0, P.Mv, P.lda) : kc_half_load_offset(wn * 4 + j, lane, wm, m0, P.Mv, P.lda);
+      b_off[j] = BKC ? kc_half_load_offset(wn * 4 + j, lane, wm, n0, P.Nv, P.ldb) : km_load_offset(wn * 4 + j, lane, n0, P.Nv, P.ldb);
     }
     const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(smem));
-    // this wave's 8 instructions of full tile kt; kt is clamped so that a load issued past the last full tile
-    // re-reads a valid tile into a stage nobody reads any more
+    // address of what tile kt's part holds: k = 32 kt for a K-major operand, the K step's first k for a K-contiguous one
+    auto a_tile_ptr = [&](int kt) { return AKM ? Abase + kt * a_tile : Abase + (kt >> 1) * (2 * kMfmaBK); };
+    auto b_tile_ptr = [&](int kt) { return BKC ? Bbase + (kt >> 1) * (2 * kMfmaBK) : Bbase + kt * b_tile; };
+    // this wave's 8 instructions of tile kt of the main loop; kt is clamped so that a load issued past the loop's
+    // last tile re-reads valid memory into a stage nobody reads any more
     auto load_tile = [&](int kt) {
-      const int kc = min(kt, nk32 - 1);
-      const bf16_bits* ab = Abase + kc * a_tile;
-      const bf16_bits* bb = Bbase + kc * b_tile;
+      const int kc = min(kt, nkt - 1);
+      const bf16_bits* ab = a_tile_ptr(kc);
+      const bf16_bits* bb = b_tile_ptr(kc);
       const uint32_t sa = lds0 + (kt % kNumStages) * kStage + wn * 4096;
 #pragma unroll
       for (int j = 0; j < 4; ++j) global_to_lds16(ab, a_off[j], sa + j * 1024);
@@ -197,12 +223,15 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const Problem* _
       unsigned char* sa = smem + stage * kStage + wn * 4096 + lane * 16;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        *reinterpret_cast<u32x4_t*>(sa + j * 1024) = tail_chunk(AKM, ab, a_off[j], wn * 4 + j, k0);
-        *reinterpret_cast<u32x4_t*>(sa + kStageA + j * 1024) = tail_chunk(!BKC, bb, b_off[j], wn * 4 + j, k0);
+        const int q = wn * 4 + j;
+        const int ao = AKM ? km_load_offset(q, lane, m0, P.Mv, P.lda) : kc_load_offset(q, lane, m0, P.Mv, P.lda);
+        const int bo = BKC ? kc_load_offset(q, lane, n0, P.Nv, P.ldb) : km_load_offset(q, lane, n0, P.Nv, P.ldb);
+        *reinterpret_cast<u32x4_t*>(sa + j * 1024) = tail_chunk(AKM, ab, ao, q, k0);
+        *reinterpret_cast<u32x4_t*>(sa + kStageA + j * 1024) = tail_chunk(!BKC, bb, bo, q, k0);
       }
       GSPMD_WAIT_ALL();
     };
-    // ---- fragment read offsets inside a stage
+    // ---- fragment read offsets inside a stage, for the tail's [256][32] / [32][256] parts
     const int a_frag = AKM ? km_frag_offset(wm * 128, lane) : kc_frag_offset(wm * 128, lane);
     const int b_frag = kStageA + (BKC ? kc_frag_offset(wn * 64, lane) : km_frag_offset(wn * 64, lane));
     // fragment reads and MFMAs of one K tile in compiler-scheduled form (what is left of K after the assembly loop)
@@ -242,19 +271,23 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const Problem* _
       __builtin_amdgcn_s_waitcnt(waitcnt_imm(8, 0));
       __builtin_amdgcn_s_barrier();
       {   // ---- K loop over the full 64-wide steps: hand-scheduled assembly, see gen_mainloop.py for the register plan
-        const uint32_t ard = lds0 + a_frag, brd = lds0 + b_frag;
-        const int first = min(4 + wm, nk32 - 1);          // group 0 goes on with tiles 4, 6, ..; group 1 with 5, 7, ..
-        unsigned long long aptr = reinterpret_cast<unsigned long long>(Abase + first * a_tile);
-        unsigned long long bptr = reinterpret_cast<unsigned long long>(Bbase + first * b_tile);
-        uint32_t nadv = (nk32 - 1 - first) / 2;
+        // a K-contiguous operand is read from the part that holds this wave's rows: half wm of the lhs, wn >> 1 of the rhs
+        const uint32_t ard = lds0 + (AKM ? a_frag : kc_half_frag_offset(0, lane));
+        const uint32_t brd = lds0 + (BKC ? kStageA + kc_half_frag_offset((wn & 1) * 64, lane) : b_frag);
+        uint32_t astage = wm * kStage, bstage = (wn >> 1) * kStage;
+        const int first = min(4 + wm, nkt - 1);           // group 0 goes on with tiles 4, 6, ..; group 1 with 5, 7, ..
+        unsigned long long aptr = reinterpret_cast<unsigned long long>(a_tile_ptr(first));
+        unsigned long long bptr = reinterpret_cast<unsigned long long>(b_tile_ptr(first));
+        uint32_t nadv = (nkt - 1 - first) / 2;
         const uint32_t wrbase = lds0 + wn * 4096;
         uint32_t wstage = ((4 + wm) % kNumStages) * kStage, rstage = 0;
         uint32_t nkr = nk64;
-        const uint32_t astep = static_cast<uint32_t>(a_tile) * 4, bstep = static_cast<uint32_t>(b_tile) * 4;   // two tiles, bytes
+        const uint32_t astep = static_cast<uint32_t>(a_tile) * 4, bstep = static_cast<uint32_t>(b_tile) * 4;   // one K step, bytes
 #define GSPMD_MAINLOOP_OPERANDS \
         : "+{v[0:15]}"(acc[0]), "+{v[16:31]}"(acc[1]), "+{v[32:47]}"(acc[2]), "+{v[48:63]}"(acc[3]), \
           "+{v[64:79]}"(acc[4]), "+{v[80:95]}"(acc[5]), "+{v[96:111]}"(acc[6]), "+{v[112:127]}"(acc[7]), \
-          "+{s[40:41]}"(aptr), "+{s[42:43]}"(bptr), "+{s45}"(nkr), "+{s46}"(nadv), "+{s52}"(wstage), "+{s53}"(rstage) \
+          "+{s[40:41]}"(aptr), "+{s[42:43]}"(bptr), "+{s45}"(nkr), "+{s46}"(nadv), "+{s52}"(wstage), "+{s53}"(rstage), \
+          "+{s55}"(astage), "+{s56}"(bstage) \
         : [ard] "v"(ard), [brd] "v"(brd), [ao0] "v"(a_off[0]), [ao1] "v"(a_off[1]), [ao2] "v"(a_off[2]), [ao3] "v"(a_off[3]), \
           [bo0] "v"(b_off[0]), [bo1] "v"(b_off[1]), [bo2] "v"(b_off[2]), [bo3] "v"(b_off[3]), "{s44}"(wrbase), "{s47}"(bstep), "{s54}"(astep) \
         : GSPMD_MAINLOOP_CLOBBERS
