@@ -193,7 +193,8 @@ def main():
     # ------------------------------------------------------------------ the other configs
     if not args.headline_only:
         others = {}
-        for make in (wl.ksplit, wl.moe, wl.mesh2d, wl.ffn_second, wl.moe_second, wl.ffn_wgrad, wl.ffn_dgrad):
+        for make in (wl.ksplit, wl.moe, wl.mesh2d, wl.ffn_second, lambda: wl.ffn_second(scatter=True), wl.moe_second, wl.ffn_wgrad,
+                     wl.ffn_dgrad):
             ww = make()
             s2 = Staged(ww)
             wall, ev = timed(s2, max(10, args.steps // 2), max(3, args.warmup // 2))

@@ -55,8 +55,14 @@ typedef enum {
   GSPMD_AXIS_BATCH = 1,       /* the same batch dimension of lhs, rhs and out */
   GSPMD_AXIS_LHS_FREE = 2,    /* a non-contracting lhs dimension and the matching out dimension */
   GSPMD_AXIS_RHS_FREE = 3,    /* a non-contracting rhs dimension and the matching out dimension */
-  GSPMD_AXIS_CONTRACTING = 4  /* the same contracting dimension of lhs and rhs; out holds a partial sum */
+  GSPMD_AXIS_CONTRACTING = 4, /* the same contracting dimension of lhs and rhs; out holds a partial sum */
+  GSPMD_AXIS_CONTRACTING_SCATTER = 5 /* as CONTRACTING, and an out dimension is split on it too: after the sum every
+                                        partition keeps its slice (ReduceScatter = AllReduce + DynamicSlice, Section 4.2) */
 } gspmd_axis_class;
+
+/* Elementwise function applied to the finished sum before it is stored (the feed-forward layer of Section 5.1 is
+ * Relu(x W_in) W_out). */
+typedef enum { GSPMD_EPILOGUE_NONE = 0, GSPMD_EPILOGUE_RELU = 1 } gspmd_epilogue;
 
 /* Device mesh (Section 3.1): `device_ids` is the row-major tensor of partition ids,
  * prod(shape) entries, a permutation of 0..P-1.  Host memory. */
@@ -179,7 +185,10 @@ int32_t gspmd_dot_workspace_bytes(const gspmd_mesh* mesh, const gspmd_dot_dims* 
  * Positions >= valid length are masked to 0 in both operands along contracting dims and never
  * read along any dim (Section 4.1); out's padded region is written as 0.
  * If a mesh dimension is GSPMD_AXIS_CONTRACTING, out must be f32 and receives this
- * partition's partial sum (to be combined with gspmd_reduce_partials).
+ * partition's partial sum (to be combined with gspmd_reduce_partials); `epilogue` must then be
+ * GSPMD_EPILOGUE_NONE, and GSPMD_AXIS_CONTRACTING_SCATTER is GSPMD_ERR_UNSUPPORTED here (a slice of a
+ * sum exists only after the exchange: use gspmd_grouped_dot).
+ * epilogue: a gspmd_epilogue applied to every valid output element; padding stays 0.
  * lhs_fill (host, nullable): for an lhs with exactly one non-contracting dimension, the number
  * of occupied positions of that dimension per GLOBAL batch entry (row-major over the global
  * batch dims); rows at global position >= fill are masked and their out rows are 0
@@ -190,7 +199,7 @@ int32_t gspmd_local_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
                         const gspmd_shard_buf* lhs, const gspmd_sharding* lhs_sh,
                         const gspmd_shard_buf* rhs, const gspmd_sharding* rhs_sh,
                         const gspmd_shard_buf* out, const gspmd_sharding* out_sh,
-                        int64_t partition_id, const int64_t* lhs_fill,
+                        int64_t partition_id, const int64_t* lhs_fill, int32_t epilogue,
                         void* workspace, int64_t workspace_bytes, void* hip_stream);
 
 /* The local Dots of ALL partitions of the mesh in one ragged grouped launch
@@ -200,12 +209,14 @@ int32_t gspmd_local_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
  * If a mesh dimension is GSPMD_AXIS_CONTRACTING, fp32 partials go to the workspace and are
  * summed in ascending mesh-coordinate order into the out shard of every member of the reduce
  * group (the AllReduce of Section 4.2; members may share one buffer, written once); out may
- * then be bf16 or f32. */
+ * then be bf16 or f32.  On a GSPMD_AXIS_CONTRACTING_SCATTER dimension every member receives only
+ * its slice of the sum along the out dimension split there (ReduceScatter; the partials in the
+ * workspace have that dimension whole).  `epilogue` is applied after the sum. */
 int32_t gspmd_grouped_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
                           const gspmd_shard_buf* lhs_shards, const gspmd_sharding* lhs_sh,
                           const gspmd_shard_buf* rhs_shards, const gspmd_sharding* rhs_sh,
                           const gspmd_shard_buf* out_shards, const gspmd_sharding* out_sh,
-                          const int64_t* lhs_fill,
+                          const int64_t* lhs_fill, int32_t epilogue,
                           void* workspace, int64_t workspace_bytes, void* hip_stream);
 
 /* out[i] = partials[0][i] + partials[1][i] + ... + partials[n_partials-1][i] in fp32, in that

@@ -18,6 +18,12 @@ What it states:
   OUT (the AllReduce of Section 4.2).
 * Section 4.1: padded positions are replaced by the identity of the reduction
   (0 for a sum) before they can contribute.
+* Section 4.2: a ReduceScatter is an AllReduce followed by each partition's
+  DynamicSlice of the reduced data.  So a partition whose out sharding splits an
+  output dimension over the mesh dimension that carries the sum must hold
+  `expected_out_shard(full sum, out mapping)`; no separate function is needed.
+* Section 5.1: the feed-forward layer is Relu(x W_in) W_out with an elementwise
+  Relu, max(x, 0), applied to the finished (fully summed) first product.
 
 Arithmetic is float64 on the exact input values (bf16 or fp32 widened without
 rounding).  No blocking, fusion or reordering beyond the definition: operands
@@ -138,6 +144,11 @@ def expected_partial(lhs: np.ndarray, rhs: np.ndarray, dims, mesh_shape, device_
         shape[d] = -1
         b = b * keep.reshape(shape)
     return dot_general(a, b, lhs_batch, rhs_batch, lhs_contract, rhs_contract)
+
+
+def relu(x: np.ndarray) -> np.ndarray:
+    """Elementwise max(x, 0) of Section 5.1's feed-forward layer; NaN stays NaN."""
+    return np.maximum(x, 0.0)
 
 
 def error_metrics(got: np.ndarray, ref: np.ndarray) -> Tuple[float, float]:

@@ -7,7 +7,8 @@ from dataclasses import dataclass
 from typing import List, Optional, Sequence, Tuple
 
 F32, BF16 = 0, 1
-AXIS_UNUSED, AXIS_BATCH, AXIS_LHS_FREE, AXIS_RHS_FREE, AXIS_CONTRACTING = range(5)
+AXIS_UNUSED, AXIS_BATCH, AXIS_LHS_FREE, AXIS_RHS_FREE, AXIS_CONTRACTING, AXIS_CONTRACTING_SCATTER = range(6)
+EPILOGUE_NONE, EPILOGUE_RELU = 0, 1
 LAYOUT_LHS_K_MAJOR, LAYOUT_RHS_K_CONTIGUOUS = 1, 2
 
 EXPORTED_SYMBOLS = (
@@ -70,8 +71,8 @@ def load_library():
     lib.gspmd_shard_bounds.argtypes = [pm, ps, C.c_int64, pi64, pi64, pi64]
     lib.gspmd_classify_dot.argtypes = [pm, pd, ps, ps, ps, pi32]
     lib.gspmd_dot_workspace_bytes.argtypes = [pm, pd, ps, ps, ps, C.c_int64, C.c_int32, pi64]
-    lib.gspmd_local_dot.argtypes = [pm, pd, pb, ps, pb, ps, pb, ps, C.c_int64, pi64, C.c_void_p, C.c_int64, C.c_void_p]
-    lib.gspmd_grouped_dot.argtypes = [pm, pd, pb, ps, pb, ps, pb, ps, pi64, C.c_void_p, C.c_int64, C.c_void_p]
+    lib.gspmd_local_dot.argtypes = [pm, pd, pb, ps, pb, ps, pb, ps, C.c_int64, pi64, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p]
+    lib.gspmd_grouped_dot.argtypes = [pm, pd, pb, ps, pb, ps, pb, ps, pi64, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p]
     lib.gspmd_reduce_partials.argtypes = [C.POINTER(C.c_void_p), C.c_int32, C.c_int64, C.c_void_p, C.c_int32, C.c_void_p]
     lib.gspmd_shard_extract.argtypes = [pm, ps, C.c_int64, C.c_void_p, pb, C.c_uint32, C.c_void_p]
     lib.gspmd_shard_assemble.argtypes = [pm, ps, C.c_int64, pb, C.c_void_p, C.c_void_p]
@@ -233,23 +234,24 @@ def _fill(fill):
 
 def local_dot(mesh: Mesh, dims: DotDims, lhs: ShardBuf, lhs_sh: Sharding, rhs: ShardBuf, rhs_sh: Sharding,
               out: ShardBuf, out_sh: Sharding, partition_id: int, lhs_fill=None,
-              workspace: int = 0, workspace_bytes: int = 0, stream: int = 0) -> None:
+              workspace: int = 0, workspace_bytes: int = 0, stream: int = 0, epilogue: int = EPILOGUE_NONE) -> None:
     m, d, a, b, o = mesh._c(), dims._c(), lhs_sh._c(), rhs_sh._c(), out_sh._c()
     la, rb, ob = lhs._c(), rhs._c(), out._c()
     _check(load_library().gspmd_local_dot(C.byref(m), C.byref(d), C.byref(la), C.byref(a), C.byref(rb), C.byref(b),
-                                          C.byref(ob), C.byref(o), int(partition_id), _fill(lhs_fill),
+                                          C.byref(ob), C.byref(o), int(partition_id), _fill(lhs_fill), int(epilogue),
                                           C.c_void_p(workspace), int(workspace_bytes), C.c_void_p(stream)), "gspmd_local_dot")
 
 
 def grouped_dot(mesh: Mesh, dims: DotDims, lhs_shards: Sequence[ShardBuf], lhs_sh: Sharding,
                 rhs_shards: Sequence[ShardBuf], rhs_sh: Sharding, out_shards: Sequence[ShardBuf], out_sh: Sharding,
-                lhs_fill=None, workspace: int = 0, workspace_bytes: int = 0, stream: int = 0) -> None:
+                lhs_fill=None, workspace: int = 0, workspace_bytes: int = 0, stream: int = 0,
+                epilogue: int = EPILOGUE_NONE) -> None:
     P = mesh.n_partitions
     if not (len(lhs_shards) == len(rhs_shards) == len(out_shards) == P):
         raise ValueError("one shard buffer per partition is required")
     m, d, a, b, o = mesh._c(), dims._c(), lhs_sh._c(), rhs_sh._c(), out_sh._c()
     _check(load_library().gspmd_grouped_dot(C.byref(m), C.byref(d), _bufs(lhs_shards), C.byref(a), _bufs(rhs_shards), C.byref(b),
-                                            _bufs(out_shards), C.byref(o), _fill(lhs_fill),
+                                            _bufs(out_shards), C.byref(o), _fill(lhs_fill), int(epilogue),
                                             C.c_void_p(workspace), int(workspace_bytes), C.c_void_p(stream)), "gspmd_grouped_dot")
 
 

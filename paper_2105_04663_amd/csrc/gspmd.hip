@@ -54,7 +54,7 @@ bool mfma_eligible(const std::vector<Problem>& ps, int32_t in_dtype, int32_t lay
 }
 
 // Upload the problem table into the workspace and launch the contraction over all tiles.
-int32_t launch_problems(std::vector<Problem>& ps, int32_t layout, int32_t in_dtype, int32_t out_dtype,
+int32_t launch_problems(std::vector<Problem>& ps, int32_t layout, int32_t in_dtype, int32_t out_dtype, int32_t epilogue,
                         void* workspace, int64_t workspace_bytes, hipStream_t stream) {
   // problems with an empty static output block write nothing
   ps.erase(std::remove_if(ps.begin(), ps.end(), [](const Problem& p) { return p.Ms == 0 || p.Ns == 0; }), ps.end());
@@ -71,16 +71,16 @@ int32_t launch_problems(std::vector<Problem>& ps, int32_t layout, int32_t in_dty
   const Problem* tab = static_cast<const Problem*>(workspace);
   const int n = static_cast<int>(ps.size());
   if (mfma) {
-    if (!launch_dot_mfma(tab, n, static_cast<int>(tiles), layout, out_dtype, stream)) return GSPMD_ERR_DEVICE;
+    if (!launch_dot_mfma(tab, n, static_cast<int>(tiles), layout, out_dtype, epilogue, stream)) return GSPMD_ERR_DEVICE;
     return GSPMD_OK;
   }
   const dim3 grid(static_cast<unsigned>(tiles)), block(256);
   if (in_dtype == GSPMD_F32)
-    hipLaunchKernelGGL((dot_fallback_kernel<float, float>), grid, block, 0, stream, tab, n, layout);
+    hipLaunchKernelGGL((dot_fallback_kernel<float, float>), grid, block, 0, stream, tab, n, layout, epilogue);
   else if (out_dtype == GSPMD_F32)
-    hipLaunchKernelGGL((dot_fallback_kernel<bf16_bits, float>), grid, block, 0, stream, tab, n, layout);
+    hipLaunchKernelGGL((dot_fallback_kernel<bf16_bits, float>), grid, block, 0, stream, tab, n, layout, epilogue);
   else
-    hipLaunchKernelGGL((dot_fallback_kernel<bf16_bits, bf16_bits>), grid, block, 0, stream, tab, n, layout);
+    hipLaunchKernelGGL((dot_fallback_kernel<bf16_bits, bf16_bits>), grid, block, 0, stream, tab, n, layout, epilogue);
   return hipGetLastError() == hipSuccess ? GSPMD_OK : GSPMD_ERR_DEVICE;
 }
 
@@ -105,9 +105,79 @@ int32_t launch_reduce(const float* const* partials, int n_partials, int64_t rows
   return hipGetLastError() == hipSuccess ? GSPMD_OK : GSPMD_ERR_DEVICE;
 }
 
+bool is_contracting(int32_t c) { return c == GSPMD_AXIS_CONTRACTING || c == GSPMD_AXIS_CONTRACTING_SCATTER; }
+
 bool has_contracting(const gspmd_mesh* mesh, const int32_t* cls) {
-  for (int a = 0; a < mesh->rank; ++a) if (cls[a] == GSPMD_AXIS_CONTRACTING) return true;
+  for (int a = 0; a < mesh->rank; ++a) if (is_contracting(cls[a])) return true;
   return false;
+}
+
+bool has_scatter(const gspmd_mesh* mesh, const int32_t* cls) {
+  for (int a = 0; a < mesh->rank; ++a) if (cls[a] == GSPMD_AXIS_CONTRACTING_SCATTER) return true;
+  return false;
+}
+
+bool is_epilogue(int32_t e) { return e == GSPMD_EPILOGUE_NONE || e == GSPMD_EPILOGUE_RELU; }
+
+// The sharding of a partition's partial sum: the out sharding with the dimensions that a scatter mesh dimension
+// splits made whole again (the slice is taken after the sum).
+void partial_mapping(const gspmd_mesh* mesh, const int32_t* cls, const gspmd_sharding* out_sh, int32_t* map) {
+  for (int i = 0; i < out_sh->rank; ++i) {
+    const int a = out_sh->dims_mapping[i];
+    map[i] = (a >= 0 && a < mesh->rank && cls[a] == GSPMD_AXIS_CONTRACTING_SCATTER) ? -1 : a;
+  }
+}
+
+// out shard of partition `pid` = epilogue(sum of the group's partials) restricted to the shard's place in them.
+int32_t launch_reduce_scatter(const gspmd_mesh* mesh, const gspmd_sharding* out_sh, const gspmd_sharding* part_sh, int64_t pid,
+                              const float* const* partials, int n_partials, const gspmd_shard_buf* out, int32_t epilogue,
+                              hipStream_t stream) {
+  Bounds ob, pb;
+  int32_t st;
+  if ((st = shard_bounds(mesh, out_sh, pid, &ob)) != GSPMD_OK) return st;
+  if ((st = shard_bounds(mesh, part_sh, pid, &pb)) != GSPMD_OK) return st;
+  ScatterDesc d;
+  std::memset(&d, 0, sizeof(d));
+  const int r = ob.rank, last = r - 1;
+  d.rank = r;
+  int64_t rows = 1, in_stride = 1;
+  for (int i = last; i >= 0; --i) {
+    if (ob.shard[i] > INT32_MAX) return GSPMD_ERR_UNSUPPORTED;
+    d.shard[i] = static_cast<int32_t>(ob.shard[i]);
+    d.valid[i] = static_cast<int32_t>(ob.valid[i]);
+    d.in_off[i] = ob.offset[i] - pb.offset[i];
+    d.in_stride[i] = in_stride;
+    in_stride *= pb.shard[i];
+    if (i < last) rows *= ob.shard[i];
+  }
+  if (rows > INT32_MAX) return GSPMD_ERR_UNSUPPORTED;
+  d.rows = static_cast<int32_t>(rows);
+  d.out_stride[last] = 1;
+  if (r >= 2) {
+    const int64_t rs = out->row_stride > 0 ? out->row_stride : ob.shard[last];
+    if (rs < ob.shard[last]) return GSPMD_ERR_BAD_BUFFER;
+    d.out_stride[r - 2] = rs;
+    for (int i = r - 3; i >= 0; --i) d.out_stride[i] = d.out_stride[i + 1] * ob.shard[i + 1];
+  }
+  if (rows == 0 || ob.shard[last] == 0) return GSPMD_OK;
+  PartialPtrs pp;
+  uintptr_t bits = reinterpret_cast<uintptr_t>(out->data);
+  for (int i = 0; i < kMaxPartials; ++i) pp.p[i] = nullptr;
+  for (int i = 0; i < n_partials; ++i) { pp.p[i] = partials[i]; bits |= reinterpret_cast<uintptr_t>(partials[i]); }
+  bool vec = !(bits & 15) && !(ob.shard[last] & 3) && !(pb.shard[last] & 3) && !(d.in_off[last] & 3);
+  for (int i = 0; i < last; ++i) vec = vec && !(d.in_stride[i] & 3) && !(d.out_stride[i] & 3);
+  const int64_t cols_v = (ob.shard[last] + (vec ? 3 : 0)) / (vec ? 4 : 1);
+  // about 8192 workgroups; each thread walks down its column of rows
+  const int64_t gx = (cols_v + 255) / 256;
+  const dim3 block(256), grid(static_cast<unsigned>(gx), static_cast<unsigned>(std::min<int64_t>(rows, std::max<int64_t>(1, 8192 / gx))));
+  if (out->dtype == GSPMD_F32) {
+    if (vec) hipLaunchKernelGGL((reduce_scatter_kernel<float, 4>), grid, block, 0, stream, d, pp, n_partials, static_cast<float*>(out->data), epilogue);
+    else hipLaunchKernelGGL((reduce_scatter_kernel<float, 1>), grid, block, 0, stream, d, pp, n_partials, static_cast<float*>(out->data), epilogue);
+  } else {
+    if (vec) hipLaunchKernelGGL((reduce_scatter_kernel<bf16_bits, 4>), grid, block, 0, stream, d, pp, n_partials, static_cast<bf16_bits*>(out->data), epilogue);
+    else hipLaunchKernelGGL((reduce_scatter_kernel<bf16_bits, 1>), grid, block, 0, stream, d, pp, n_partials, static_cast<bf16_bits*>(out->data), epilogue);
+  }
+  return hipGetLastError() == hipSuccess ? GSPMD_OK : GSPMD_ERR_DEVICE;
 }
 
 }  // namespace
@@ -274,9 +344,12 @@ int32_t gspmd_dot_workspace_bytes(const gspmd_mesh* mesh, const gspmd_dot_dims* 
   if (pid < -1 || pid >= P) return GSPMD_ERR_PARTITION_RANGE;
   int64_t n_prob = 0, partial_bytes = 0;
   const bool contracting = has_contracting(mesh, cls);
+  int32_t pmap[kMaxRank];
+  partial_mapping(mesh, cls, out_sh, pmap);
+  const gspmd_sharding part_sh{out_sh->rank, out_sh->global_shape, pmap};
   for (int64_t p = (pid < 0 ? 0 : pid); p < (pid < 0 ? P : pid + 1); ++p) {
     int64_t n, e;
-    if ((st = count_partition(mesh, r, lhs_sh, rhs_sh, out_sh, p, &n, &e)) != GSPMD_OK) return st;
+    if ((st = count_partition(mesh, r, lhs_sh, rhs_sh, &part_sh, p, &n, &e)) != GSPMD_OK) return st;
     n_prob += n;
     if (pid < 0 && contracting) partial_bytes += round_up(e * 4, kWsAlign);
   }
@@ -288,15 +361,17 @@ int32_t gspmd_local_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
                         const gspmd_shard_buf* lhs, const gspmd_sharding* lhs_sh,
                         const gspmd_shard_buf* rhs, const gspmd_sharding* rhs_sh,
                         const gspmd_shard_buf* out, const gspmd_sharding* out_sh,
-                        int64_t pid, const int64_t* lhs_fill,
+                        int64_t pid, const int64_t* lhs_fill, int32_t epilogue,
                         void* workspace, int64_t workspace_bytes, void* hip_stream) {
   int32_t st;
+  if (!is_epilogue(epilogue)) return GSPMD_ERR_UNSUPPORTED;
   if ((st = check_buf(lhs)) != GSPMD_OK || (st = check_buf(rhs)) != GSPMD_OK || (st = check_buf(out)) != GSPMD_OK) return st;
   DotRoles r;
   int32_t cls[kMaxRank];
   if ((st = analyse_dot(mesh, dims, lhs_sh, rhs_sh, out_sh, &r, cls)) != GSPMD_OK) return st;
   if (lhs->dtype != rhs->dtype) return GSPMD_ERR_UNSUPPORTED;
-  if (has_contracting(mesh, cls) && out->dtype != GSPMD_F32) return GSPMD_ERR_UNSUPPORTED;
+  if (has_contracting(mesh, cls) && (out->dtype != GSPMD_F32 || epilogue != GSPMD_EPILOGUE_NONE)) return GSPMD_ERR_UNSUPPORTED;
+  if (has_scatter(mesh, cls)) return GSPMD_ERR_UNSUPPORTED;   // a slice of a sum exists only after the exchange
   std::vector<Problem> ps;
   int64_t elems = 0;
   int32_t layout = 0;
@@ -304,16 +379,17 @@ int32_t gspmd_local_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
     return st;
   for (const auto& p : ps)
     if ((p.Kv && (!p.A || !p.B)) || !p.C) return GSPMD_ERR_NULL;
-  return launch_problems(ps, layout, lhs->dtype, out->dtype, workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
+  return launch_problems(ps, layout, lhs->dtype, out->dtype, epilogue, workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
 }
 
 int32_t gspmd_grouped_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
                           const gspmd_shard_buf* lhs_shards, const gspmd_sharding* lhs_sh,
                           const gspmd_shard_buf* rhs_shards, const gspmd_sharding* rhs_sh,
                           const gspmd_shard_buf* out_shards, const gspmd_sharding* out_sh,
-                          const int64_t* lhs_fill,
+                          const int64_t* lhs_fill, int32_t epilogue,
                           void* workspace, int64_t workspace_bytes, void* hip_stream) {
   if (!lhs_shards || !rhs_shards || !out_shards) return GSPMD_ERR_NULL;
+  if (!is_epilogue(epilogue)) return GSPMD_ERR_UNSUPPORTED;
   DotRoles r;
   int32_t cls[kMaxRank];
   int32_t st;
@@ -336,9 +412,12 @@ int32_t gspmd_grouped_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kWsAlign - 1)) || workspace_bytes < need) return GSPMD_ERR_WORKSPACE;
   int64_t n_bound = 0;
   std::vector<int64_t> elems(static_cast<size_t>(P), 0);
+  int32_t pmap[kMaxRank];
+  partial_mapping(mesh, cls, out_sh, pmap);
+  const gspmd_sharding part_sh{out_sh->rank, out_sh->global_shape, pmap};   // == out_sh unless a sum is scattered
   for (int64_t p = 0; p < P; ++p) {
     int64_t n;
-    if ((st = count_partition(mesh, r, lhs_sh, rhs_sh, out_sh, p, &n, &elems[static_cast<size_t>(p)])) != GSPMD_OK) return st;
+    if ((st = count_partition(mesh, r, lhs_sh, rhs_sh, &part_sh, p, &n, &elems[static_cast<size_t>(p)])) != GSPMD_OK) return st;
     n_bound += n;
   }
   char* partial_base = static_cast<char*>(workspace) + round_up(std::max<int64_t>(n_bound, 1) * static_cast<int64_t>(sizeof(Problem)), kWsAlign);
@@ -364,13 +443,14 @@ int32_t gspmd_grouped_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
     }
     int64_t e = 0;
     const size_t before = ps.size();
-    st = plan_partition(mesh, r, &lhs_shards[p], lhs_sh, &rhs_shards[p], rhs_sh, &out_shards[p], out_sh, p, lhs_fill,
+    st = plan_partition(mesh, r, &lhs_shards[p], lhs_sh, &rhs_shards[p], rhs_sh, &out_shards[p], &part_sh, p, lhs_fill,
                         contracting ? partial[static_cast<size_t>(p)] : nullptr, &ps, &e, &layout);
     if (st != GSPMD_OK) return st;
     for (size_t i = before; i < ps.size(); ++i)
       if ((ps[i].Kv && (!ps[i].A || !ps[i].B)) || !ps[i].C) return GSPMD_ERR_NULL;
   }
-  st = launch_problems(ps, layout, in_dtype, contracting ? GSPMD_F32 : out_dtype, workspace, workspace_bytes, stream);
+  st = launch_problems(ps, layout, in_dtype, contracting ? GSPMD_F32 : out_dtype, contracting ? GSPMD_EPILOGUE_NONE : epilogue,
+                       workspace, workspace_bytes, stream);
   if (st != GSPMD_OK || !contracting) return st;
 
   // Sum the partials of each reduce group (partitions that differ only along contracting
@@ -382,7 +462,7 @@ int32_t gspmd_grouped_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
     std::vector<int64_t> key;
     int64_t pos = 0;
     for (int a = 0; a < mesh->rank; ++a) {
-      if (cls[a] == GSPMD_AXIS_CONTRACTING) pos = pos * mesh->shape[a] + coords[a];
+      if (is_contracting(cls[a])) pos = pos * mesh->shape[a] + coords[a];
       else key.push_back(coords[a]);
     }
     groups[key].emplace_back(pos, p);
@@ -393,19 +473,13 @@ int32_t gspmd_grouped_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
     if (members.size() > static_cast<size_t>(kMaxPartials)) return GSPMD_ERR_UNSUPPORTED;
     std::vector<const float*> ptrs;
     for (auto& m : members) ptrs.push_back(partial[static_cast<size_t>(m.second)]);
-    Bounds ob;
-    if ((st = shard_bounds(mesh, out_sh, members[0].second, &ob)) != GSPMD_OK) return st;
-    const int64_t cols = ob.shard[ob.rank - 1];
-    const int64_t rows = cols ? elems[static_cast<size_t>(members[0].second)] / cols : 0;
     std::vector<void*> written;
     for (auto& m : members) {
       const gspmd_shard_buf& o = out_shards[m.second];
       if (std::find(written.begin(), written.end(), o.data) != written.end()) continue;
       written.push_back(o.data);
-      // outer dims of the out shard are dense over row_stride, so it is a rows x cols matrix
-      const int64_t ld_out = (ob.rank >= 2 && o.row_stride > 0) ? o.row_stride : cols;
-      if (ld_out < cols) return GSPMD_ERR_BAD_BUFFER;
-      if ((st = launch_reduce(ptrs.data(), static_cast<int>(ptrs.size()), rows, cols, cols, o.data, ld_out, o.dtype, stream)) != GSPMD_OK)
+      if ((st = launch_reduce_scatter(mesh, out_sh, &part_sh, m.second, ptrs.data(), static_cast<int>(ptrs.size()), &o, epilogue,
+                                      stream)) != GSPMD_OK)
         return st;
     }
   }

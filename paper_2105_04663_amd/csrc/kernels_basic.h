@@ -31,6 +31,11 @@ template <typename T> __device__ __forceinline__ void store_from_float(T* p, flo
 template <> __device__ __forceinline__ void store_from_float<float>(float* p, float v) { *p = v; }
 template <> __device__ __forceinline__ void store_from_float<bf16_bits>(bf16_bits* p, float v) { *p = float_to_bf16(v); }
 
+// Elementwise epilogue on a finished sum (gspmd_epilogue); NaN stays NaN.
+__device__ __forceinline__ float apply_epilogue(float v, int epilogue) {
+  return (epilogue == GSPMD_EPILOGUE_RELU && v < 0.f) ? 0.f : v;
+}
+
 // Which problem owns output tile `tile`: the last entry whose tile_begin <= tile.
 __device__ __forceinline__ int find_problem(const Problem* __restrict__ tab, int n_prob, int tile) {
   int lo = 0, hi = n_prob - 1;
@@ -48,7 +53,7 @@ constexpr int kGenBK = 16;
 // Every load is predicated on the valid extents (masked positions contribute 0 and are never
 // read); stores cover the static extents and write 0 outside the valid region.
 template <typename TIn, typename TOut>
-__global__ __launch_bounds__(256) void dot_fallback_kernel(const Problem* __restrict__ tab, int n_prob, int layout) {
+__global__ __launch_bounds__(256) void dot_fallback_kernel(const Problem* __restrict__ tab, int n_prob, int layout, int epilogue) {
   __shared__ float As[kGenBK][kGenTile + 4];   // [k][m]
   __shared__ float Bs[kGenBK][kGenTile + 4];   // [k][n]
   const int tile = blockIdx.x;
@@ -101,7 +106,7 @@ __global__ __launch_bounds__(256) void dot_fallback_kernel(const Problem* __rest
     for (int j = 0; j < 4; ++j) {
       const int n = n0 + tx * 4 + j;
       if (n >= P.Ns) continue;
-      const float v = (m < P.Mv && n < P.Nv) ? acc[i][j] : 0.f;
+      const float v = (m < P.Mv && n < P.Nv) ? apply_epilogue(acc[i][j], epilogue) : 0.f;
       store_from_float<TOut>(C + static_cast<int64_t>(m) * P.ldc + n, v);
     }
   }
@@ -144,6 +149,70 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(PartialPtrs ptrs, 
       acc[0] = ptrs.p[0][r * ld_in + c];
       for (int p = 1; p < n_partials; ++p) acc[0] += ptrs.p[p][r * ld_in + c];
       store_from_float<TOut>(out + r * ld_out + c, acc[0]);
+    }
+  }
+}
+
+// Sum of K-partials written to an out shard that may be a slice of the partials' extent (ReduceScatter: the sum
+// followed by each partition's DynamicSlice), any rank.  The last dimension is contiguous on both sides.
+struct ScatterDesc {
+  int32_t rank;
+  int32_t rows;                  // product of the out shard's static extents except the last
+  int32_t shard[kMaxRank];       // out shard, static extents
+  int32_t valid[kMaxRank];       // out shard, valid extents (the rest is written as 0 and never read from the partials)
+  int64_t in_off[kMaxRank];      // where the out shard starts inside the partial, per dimension
+  int64_t in_stride[kMaxRank];   // element strides of the (dense) partials
+  int64_t out_stride[kMaxRank];  // element strides of the out shard
+};
+
+// grid.x covers the last dimension in vectors of VEC, grid.y strides over the rows.  VEC = 4 needs 16-byte aligned
+// pointers and every stride, offset and extent of the last two dimensions a multiple of 4.
+template <typename TOut, int VEC>
+__global__ __launch_bounds__(256) void reduce_scatter_kernel(ScatterDesc d, PartialPtrs ptrs, int n_partials,
+                                                             TOut* __restrict__ out, int epilogue) {
+  const int last = d.rank - 1;
+  const int c = (blockIdx.x * blockDim.x + threadIdx.x) * VEC;
+  if (c >= d.shard[last]) return;
+  for (int row = blockIdx.y; row < d.rows; row += gridDim.y) {
+    int rem = row;
+    int64_t in = d.in_off[last] + c, o = c;
+    bool ok = true;
+    for (int k = last - 1; k >= 0; --k) {
+      const int x = rem % d.shard[k];
+      rem /= d.shard[k];
+      in += (x + d.in_off[k]) * d.in_stride[k];
+      o += x * d.out_stride[k];
+      ok = ok && x < d.valid[k];
+    }
+    float acc[VEC];
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) acc[j] = 0.f;
+    if (ok && c < d.valid[last]) {
+      if constexpr (VEC == 4) {
+        const float4 v = *reinterpret_cast<const float4*>(ptrs.p[0] + in);
+        acc[0] = v.x; acc[1] = v.y; acc[2] = v.z; acc[3] = v.w;
+        for (int p = 1; p < n_partials; ++p) {   // fixed ascending order: deterministic
+          const float4 w = *reinterpret_cast<const float4*>(ptrs.p[p] + in);
+          acc[0] += w.x; acc[1] += w.y; acc[2] += w.z; acc[3] += w.w;
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[j] = (c + j < d.valid[last]) ? apply_epilogue(acc[j], epilogue) : 0.f;
+      } else {
+        acc[0] = ptrs.p[0][in];
+        for (int p = 1; p < n_partials; ++p) acc[0] += ptrs.p[p][in];
+        acc[0] = apply_epilogue(acc[0], epilogue);
+      }
+    }
+    if constexpr (VEC == 4) {
+      if constexpr (sizeof(TOut) == 4) {
+        *reinterpret_cast<float4*>(out + o) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+      } else {
+        ushort4 b;
+        b.x = float_to_bf16(acc[0]); b.y = float_to_bf16(acc[1]); b.z = float_to_bf16(acc[2]); b.w = float_to_bf16(acc[3]);
+        *reinterpret_cast<ushort4*>(out + o) = b;
+      }
+    } else {
+      store_from_float<TOut>(out + o, acc[0]);
     }
   }
 }

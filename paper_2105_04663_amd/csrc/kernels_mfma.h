@@ -141,7 +141,7 @@ __device__ __forceinline__ int km_frag_offset(int base, int lane) {
 }
 
 template <typename TOut, int LAYOUT>
-__global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const Problem* __restrict__ tab, int n_prob) {
+__global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const Problem* __restrict__ tab, int n_prob, int epilogue) {
   constexpr bool AKM = (LAYOUT & GSPMD_LAYOUT_LHS_K_MAJOR) != 0, BKC = (LAYOUT & GSPMD_LAYOUT_RHS_K_CONTIGUOUS) != 0;
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   const int t = threadIdx.x, lane = t & 63;
@@ -342,7 +342,7 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const Problem* _
       if (n >= P.Ns) continue;
       float v[4];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) v[j] = (mrow && n + j < P.Nv) ? acc[bm][bn * 4 + j] : 0.f;
+      for (int j = 0; j < 4; ++j) v[j] = (mrow && n + j < P.Nv) ? apply_epilogue(acc[bm][bn * 4 + j], epilogue) : 0.f;
       if (vec_ok && n + 4 <= P.Ns) {
         if constexpr (sizeof(TOut) == 4) {
           *reinterpret_cast<float4*>(crow + n) = make_float4(v[0], v[1], v[2], v[3]);
@@ -361,7 +361,7 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const Problem* _
 }
 
 template <typename TOut, int LAYOUT>
-inline bool launch_dot_mfma_as(const Problem* tab, int n_prob, int tiles, hipStream_t stream) {
+inline bool launch_dot_mfma_as(const Problem* tab, int n_prob, int tiles, int epilogue, hipStream_t stream) {
   static bool attr_done = false;
   if (!attr_done) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(&dot_mfma_kernel<TOut, LAYOUT>),
@@ -369,17 +369,18 @@ inline bool launch_dot_mfma_as(const Problem* tab, int n_prob, int tiles, hipStr
     attr_done = true;
   }
   const dim3 grid(static_cast<unsigned>(tiles)), block(kMfmaThreads);
-  hipLaunchKernelGGL((dot_mfma_kernel<TOut, LAYOUT>), grid, block, kMfmaLds, stream, tab, n_prob);
+  hipLaunchKernelGGL((dot_mfma_kernel<TOut, LAYOUT>), grid, block, kMfmaLds, stream, tab, n_prob, epilogue);
   return hipGetLastError() == hipSuccess;
 }
 
-inline bool launch_dot_mfma(const Problem* tab, int n_prob, int tiles, int32_t layout, int32_t out_dtype, hipStream_t stream) {
+inline bool launch_dot_mfma(const Problem* tab, int n_prob, int tiles, int32_t layout, int32_t out_dtype, int epilogue,
+                            hipStream_t stream) {
   const bool f32 = out_dtype == GSPMD_F32;
   switch (layout & 3) {
-    case 0: return f32 ? launch_dot_mfma_as<float, 0>(tab, n_prob, tiles, stream) : launch_dot_mfma_as<bf16_bits, 0>(tab, n_prob, tiles, stream);
-    case 1: return f32 ? launch_dot_mfma_as<float, 1>(tab, n_prob, tiles, stream) : launch_dot_mfma_as<bf16_bits, 1>(tab, n_prob, tiles, stream);
-    case 2: return f32 ? launch_dot_mfma_as<float, 2>(tab, n_prob, tiles, stream) : launch_dot_mfma_as<bf16_bits, 2>(tab, n_prob, tiles, stream);
-    default: return f32 ? launch_dot_mfma_as<float, 3>(tab, n_prob, tiles, stream) : launch_dot_mfma_as<bf16_bits, 3>(tab, n_prob, tiles, stream);
+    case 0: return f32 ? launch_dot_mfma_as<float, 0>(tab, n_prob, tiles, epilogue, stream) : launch_dot_mfma_as<bf16_bits, 0>(tab, n_prob, tiles, epilogue, stream);
+    case 1: return f32 ? launch_dot_mfma_as<float, 1>(tab, n_prob, tiles, epilogue, stream) : launch_dot_mfma_as<bf16_bits, 1>(tab, n_prob, tiles, epilogue, stream);
+    case 2: return f32 ? launch_dot_mfma_as<float, 2>(tab, n_prob, tiles, epilogue, stream) : launch_dot_mfma_as<bf16_bits, 2>(tab, n_prob, tiles, epilogue, stream);
+    default: return f32 ? launch_dot_mfma_as<float, 3>(tab, n_prob, tiles, epilogue, stream) : launch_dot_mfma_as<bf16_bits, 3>(tab, n_prob, tiles, epilogue, stream);
   }
 }
 

@@ -151,7 +151,10 @@ int32_t analyse_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
       cls = GSPMD_AXIS_UNUSED;
     } else if (ld >= 0 && rd >= 0 && od >= 0) {
       const int bi = index_of(r->lhs_batch, nb, ld);
+      const int ci = index_of(r->lhs_contract, nc, ld);
       if (bi >= 0 && r->rhs_batch[bi] == rd && od == bi) cls = GSPMD_AXIS_BATCH;
+      // a contracting pair and, independently, some out dimension: the sum is scattered along that dimension
+      else if (ci >= 0 && r->rhs_contract[ci] == rd) cls = GSPMD_AXIS_CONTRACTING_SCATTER;
     } else if (ld >= 0 && rd < 0 && od >= 0) {
       const int fi = index_of(r->lhs_free, r->nlf, ld);
       if (fi >= 0 && od == nb + fi) cls = GSPMD_AXIS_LHS_FREE;

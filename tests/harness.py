@@ -114,16 +114,16 @@ class Staged:
         self.keep.append(ws)
         return base, n
 
-    def run_local(self, pid, fill=None, out_override=None):
+    def run_local(self, pid, fill=None, out_override=None, epilogue=0):
         base, n = self.workspace(pid, fill is not None)
         out = out_override if out_override is not None else self.out[pid][0]
         g.local_dot(self.mesh, self.dims, self.lhs[pid][0], self.lhs_sh, self.rhs[pid][0], self.rhs_sh,
-                    out, self.out_sh, pid, fill, base, n, torch.cuda.current_stream().cuda_stream)
+                    out, self.out_sh, pid, fill, base, n, torch.cuda.current_stream().cuda_stream, epilogue)
 
-    def run_grouped(self, fill=None):
+    def run_grouped(self, fill=None, epilogue=0):
         base, n = self.workspace(-1, fill is not None)
         g.grouped_dot(self.mesh, self.dims, [x[0] for x in self.lhs], self.lhs_sh, [x[0] for x in self.rhs], self.rhs_sh,
-                      [x[0] for x in self.out], self.out_sh, fill, base, n, torch.cuda.current_stream().cuda_stream)
+                      [x[0] for x in self.out], self.out_sh, fill, base, n, torch.cuda.current_stream().cuda_stream, epilogue)
 
     def out_shard(self, pid) -> np.ndarray:
         torch.cuda.synchronize()

@@ -113,6 +113,21 @@ def test_second_ffn_einsum_full_size():
     check(got, ref, "BSH,HM->BSM")
 
 
+def test_second_ffn_einsum_reduce_scatter_full_size():
+    # the same sum, but every partition keeps only its quarter of M (ReduceScatter)
+    w = wl.ffn_second(scatter=True)
+    lhs, rhs = w.draw_lhs(), w.draw_rhs()
+    st = Staged(w, lhs, rhs, row_align=8)
+    st.run_grouped()
+    torch.cuda.synchronize()
+    s_idx = sample_rows(2048, [256, 1024], seed=7, extra=4)
+    ref = od.dot_general(wl.bf16_bits_to_f64(lhs[:2][:, s_idx, :]), wl.bf16_bits_to_f64(rhs), (), (), (2,), (0,))
+    for pid in range(4):
+        out = out_tensor(st, pid).view(8, 2048, 2048)
+        got = to_f64(out[:2][:, torch.from_numpy(s_idx).cuda(), :].contiguous())
+        check(got, ref[:, :, 2048 * pid:2048 * (pid + 1)], f"BSH,HM->BSM slice {pid}")
+
+
 def test_second_moe_einsum_full_size():
     w = wl.moe_second()
     fill = w.draw_fill()

@@ -324,6 +324,86 @@ def test_backward_einsums_small():
     compare_all_shards(st, w, oracle_global(w, lhs, rhs))
 
 
+# --------------------------------------------------------------------------- ReduceScatter-shaped output, Relu
+@pytest.mark.parametrize("M,align", [(256, 8), (262, 8), (262, 0)])
+@pytest.mark.parametrize("out_dtype", ["bf16", "f32"])
+def test_reduce_scatter_along_columns(M, align, out_dtype):
+    # BSH,HM->BSM with H split over 4 partitions and the output's M split over the same mesh dimension: every partition
+    # keeps its slice of the sum (262 / 4: shards of 66, the last one 64 valid)
+    w = wl.ffn_second(B=3, S=70, H=1000, M=M, Y=4)
+    w.out_map = (-1, -1, 0)
+    w.device_ids = (2, 0, 3, 1)
+    lhs, rhs = wl.draw_normal_bf16(1, w.lhs_shape), wl.draw_normal_bf16(2, w.rhs_shape, 0.05)
+    st = Staged(w, lhs, rhs, row_align=align, out_dtype=out_dtype)
+    assert g.classify_dot(st.mesh, st.dims, st.lhs_sh, st.rhs_sh, st.out_sh) == (g.AXIS_CONTRACTING_SCATTER,)
+    st.run_grouped()
+    ref = oracle_global(w, lhs, rhs)
+    compare_all_shards(st, w, ref)
+    check(st.assemble(), ref, what="reassembled")
+    with pytest.raises(g.GspmdError) as e:     # one partition alone cannot produce a slice of the sum
+        st.run_local(0)
+    assert e.value.status == 7
+
+
+def test_reduce_scatter_along_rows_and_two_dims():
+    # weight gradient BSM,BSH->MH: B over X (contracting), the gradient's M rows scattered over X too, H over Y
+    w = wl.ffn_wgrad(B=5, S=70, M=262, H=520, X=3, Y=2)
+    w.out_map = (0, 1)
+    lhs, rhs = wl.draw_small_int_bf16(1, w.lhs_shape), wl.draw_small_int_bf16(2, w.rhs_shape)
+    st = Staged(w, lhs, rhs, row_align=8, out_dtype="f32")
+    assert g.classify_dot(st.mesh, st.dims, st.lhs_sh, st.rhs_sh, st.out_sh) == (g.AXIS_CONTRACTING_SCATTER, g.AXIS_RHS_FREE)
+    st.run_grouped()
+    ref = oracle_global(w, lhs, rhs)
+    compare_all_shards(st, w, ref, exact=True)
+    # i c1 c2 , c1 c2 j -> i j on a 2 x 2 mesh: c1 over X, c2 over Y, and the sum scattered as i over X, j over Y
+    w = _generic((37, 6, 40), (6, 40, 50), (), (), (1, 2), (0, 1), (2, 2), (-1, 0, 1), (0, 1, -1), (0, 1), out_dtype="f32")
+    lhs, rhs = wl.draw_small_int_bf16(3, w.lhs_shape), wl.draw_small_int_bf16(4, w.rhs_shape)
+    st = Staged(w, lhs, rhs, row_align=0, out_dtype="f32")
+    assert g.classify_dot(st.mesh, st.dims, st.lhs_sh, st.rhs_sh, st.out_sh) == (g.AXIS_CONTRACTING_SCATTER,) * 2
+    st.run_grouped()
+    ref = oracle_global(w, lhs, rhs)
+    compare_all_shards(st, w, ref, exact=True)
+    check(st.assemble(), ref, exact=True, what="reassembled")
+
+
+@pytest.mark.parametrize("mode", ["local", "grouped"])
+def test_relu_epilogue(mode):
+    # first feed-forward einsum with the layer's Relu fused (uneven 2 x 2 mesh, MFMA path), then the fp32 fallback
+    w = _generic((3, 50, 64), (64, 72), (), (), (2,), (0,), (2, 2), (0, -1, -1), (-1, 1), (0, -1, 1))
+    lhs, rhs = wl.draw_normal_bf16(1, w.lhs_shape), wl.draw_normal_bf16(2, w.rhs_shape, 0.05)
+    st = Staged(w, lhs, rhs, row_align=8)
+    if mode == "grouped":
+        st.run_grouped(epilogue=g.EPILOGUE_RELU)
+    else:
+        for pid in range(4):
+            st.run_local(pid, epilogue=g.EPILOGUE_RELU)
+    ref = od.relu(oracle_global(w, lhs, rhs))
+    assert (ref == 0).mean() > 0.3          # the clamp is exercised
+    compare_all_shards(st, w, ref)
+    w = wl.tiny_1d()
+    lhs, rhs = w.draw_lhs(), w.draw_rhs()
+    st = Staged(w, lhs, rhs, row_align=0)
+    st.run_grouped(epilogue=g.EPILOGUE_RELU)
+    compare_all_shards(st, w, od.relu(oracle_global(w, lhs, rhs)), fro_tol=1e-5)
+
+
+def test_relu_is_applied_after_the_sum_of_partials():
+    w = wl.ksplit(M=300, K=1000, N=264, P=4)
+    lhs, rhs = wl.draw_small_int_bf16(1, w.lhs_shape), wl.draw_small_int_bf16(2, w.rhs_shape)
+    st = Staged(w, lhs, rhs, row_align=8, out_dtype="f32")
+    st.run_grouped(epilogue=g.EPILOGUE_RELU)
+    ref = od.relu(oracle_global(w, lhs, rhs))
+    for pid in range(4):
+        check(st.out_shard(pid), ref, exact=True, what=f"pid {pid}")
+    st2 = Staged(w, lhs, rhs, row_align=8, out_dtype="f32", share_replicas=False)
+    with pytest.raises(g.GspmdError) as e:     # Relu of a partial sum is not Relu of the sum
+        st2.run_local(0, epilogue=g.EPILOGUE_RELU)
+    assert e.value.status == 7
+    with pytest.raises(g.GspmdError) as e:
+        st2.run_grouped(epilogue=9)
+    assert e.value.status == 7
+
+
 def test_second_layer_einsums_small():
     # BSH,HM->BSM with H split over 4 partitions (uneven: 1000/4 = 250, rows padded to 256) and bf16 output of the sum
     w = wl.ffn_second(B=3, S=70, H=1000, M=264, Y=4)

@@ -97,6 +97,13 @@ def test_classification_of_the_papers_examples():
     assert g.classify_dot(MESH, ffn, S((8, 16, 64), (0, -1, -1)), S((64, 128), (-1, 1)), S((8, 16, 128), (0, -1, 1))) == (g.AXIS_LHS_FREE, g.AXIS_RHS_FREE)
     # nothing split at all
     assert g.classify_dot(MESH, MM, S((64, 32), (-1, -1)), S((32, 48), (-1, -1)), S((64, 48), (-1, -1))) == (g.AXIS_UNUSED, g.AXIS_UNUSED)
+    # Table 1, "2D finalized", second einsum: bSh, hM -> bSm: H on Y contracts and the output's M is split on Y too,
+    # so the AllReduce becomes a ReduceScatter (Section 4.2)
+    ffn2 = g.DotDims((), (), (2,), (0,))
+    assert g.classify_dot(MESH, ffn2, S((8, 16, 128), (0, -1, 1)), S((128, 64), (1, -1)), S((8, 16, 64), (0, -1, 1))) == (g.AXIS_LHS_FREE, g.AXIS_CONTRACTING_SCATTER)
+    # its workspace holds partials with M whole: 32 partitions x [2, 16, 64] fp32
+    n = g.dot_workspace_bytes(MESH, ffn2, S((8, 16, 128), (0, -1, 1)), S((128, 64), (1, -1)), S((8, 16, 64), (0, -1, 1)), -1)
+    assert n == 32 * 2 * 64 + 32 * 2 * 16 * 64 * 4      # table (up to one problem per B index) + partials
 
 
 @pytest.mark.parametrize("lhs,rhs,out", [

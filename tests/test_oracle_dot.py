@@ -188,3 +188,32 @@ def test_bf16_rounding_matches_torch():
     t = torch.from_numpy(v).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
     assert np.array_equal(bits, t)
     assert np.array_equal(wl.bf16_bits_to_f32(bits), torch.from_numpy(v).to(torch.bfloat16).float().numpy())
+
+
+def test_relu_closed_form_and_hand_values():
+    # hand values, the identity relu(x) = (x + |x|) / 2, idempotence, and NaN propagation
+    x = np.array([-2.5, -0.0, 0.0, 1e-30, 3.0, -np.inf, np.inf])
+    assert od.relu(x).tolist() == [0.0, 0.0, 0.0, 1e-30, 3.0, 0.0, np.inf]
+    r = np.random.default_rng(3).standard_normal(1000)
+    assert np.array_equal(od.relu(r), (r + np.abs(r)) / 2)
+    assert np.array_equal(od.relu(od.relu(r)), od.relu(r))
+    assert np.isnan(od.relu(np.array([np.nan]))[0])
+
+
+def test_reduce_scatter_is_allreduce_then_slice():
+    # Section 4.2: the slices the members of a reduce group keep tile the fully reduced tensor exactly once
+    rng = np.random.default_rng(5)
+    lhs, rhs = rng.integers(-3, 4, (6, 10)).astype(float), rng.integers(-3, 4, (10, 7)).astype(float)
+    dims = ((), (), (1,), (0,))
+    mesh, ids = (3,), (2, 0, 1)
+    parts = [od.expected_partial(lhs, rhs, dims, mesh, ids, (-1, 0), (0, -1), p) for p in range(3)]
+    total = parts[0] + parts[1] + parts[2]
+    assert np.array_equal(total, lhs @ rhs)
+    seen = np.zeros((6, 7), dtype=int)
+    for p in range(3):
+        shard = od.expected_out_shard(total, mesh, ids, (-1, 0), p)       # out columns scattered over the same mesh dim
+        off, valid, size = ob.shard_bounds(mesh, ids, (6, 7), (-1, 0), p)
+        assert shard.shape == (6, 3) and np.array_equal(shard[:, :valid[1]], (lhs @ rhs)[:, off[1]:off[1] + valid[1]])
+        assert not shard[:, valid[1]:].any()
+        seen[:, off[1]:off[1] + valid[1]] += 1
+    assert (seen == 1).all()

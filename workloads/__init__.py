@@ -234,15 +234,16 @@ def mesh2d_uneven() -> DotWorkload:
 
 
 
-def ffn_second(B: int = 8, S: int = 2048, H: int = 32768, M: int = 8192, Y: int = 4) -> DotWorkload:
+def ffn_second(B: int = 8, S: int = 2048, H: int = 32768, M: int = 8192, Y: int = 4, scatter: bool = False) -> DotWorkload:
     """Second feed-forward einsum BSH,HM->BSM with H split over Y partitions (Section 5.1, Table 1): every partition
-    contracts its H slice and holds a partial BSM that the AllReduce / ReduceScatter sums."""
+    contracts its H slice and holds a partial BSM that the AllReduce sums; with `scatter` the output's M is split over
+    Y as well ("2D finalized" of Table 1) and the sum is a ReduceScatter."""
     return DotWorkload(
-        name="ffn_bsh_hm", cfg=7, dtype="bf16", out_dtype="bf16",
+        name="ffn_bsh_hm_rs" if scatter else "ffn_bsh_hm", cfg=7, dtype="bf16", out_dtype="bf16",
         lhs_shape=(B, S, H), rhs_shape=(H, M),
         lhs_batch=(), rhs_batch=(), lhs_contract=(2,), rhs_contract=(0,),
         mesh_shape=(Y,), device_ids=_ids(Y),
-        lhs_map=(-1, -1, 0), rhs_map=(0, -1), out_map=(-1, -1, -1), einsum="BSH,HM->BSM")
+        lhs_map=(-1, -1, 0), rhs_map=(0, -1), out_map=(-1, -1, 0 if scatter else -1), einsum="BSH,HM->BSM")
 
 
 def moe_second(E: int = 4, C: int = 1024, H: int = 32768, M: int = 8192) -> DotWorkload:
