@@ -240,6 +240,23 @@ int32_t gspmd_shard_assemble(const gspmd_mesh* mesh, const gspmd_sharding* shard
                              int64_t partition_id, const gspmd_shard_buf* shard,
                              void* global_data, void* hip_stream);
 
+/* Bytes of device workspace gspmd_reshard needs on this mesh.  Pure host work. */
+int32_t gspmd_reshard_workspace_bytes(const gspmd_mesh* mesh, int64_t* bytes);
+
+/* Resharding on the virtual mesh (Section 4.5): rewrite a tensor held under sharding `src_sh` into shard buffers under
+ * `dst_sh`.  What would be an AllGather (a split dimension becomes whole), a DynamicSlice (a whole dimension becomes
+ * split), an AllToAll (the split moves to another dimension or mesh dimension) or a CollectivePermute between real
+ * devices is here one on-GPU gather: every element of every dst shard is read from the src shard that owns it (among
+ * replicas, the one at the dst partition's own position along the mesh dimensions src is not split on).
+ * src_shards / dst_shards: host arrays of P entries indexed by partition id, same dtype everywhere; all src shards
+ * share one row_stride and so do all dst shards; partitions that hold the same data may pass the same pointer.  The
+ * two shardings must have the same global shape.  Only valid positions of src shards are read; the padded part of
+ * every dst shard is written as 0.  workspace: device, 256-byte aligned, >= gspmd_reshard_workspace_bytes(). */
+int32_t gspmd_reshard(const gspmd_mesh* mesh,
+                      const gspmd_sharding* src_sh, const gspmd_shard_buf* src_shards,
+                      const gspmd_sharding* dst_sh, const gspmd_shard_buf* dst_shards,
+                      void* workspace, int64_t workspace_bytes, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -9,6 +9,6 @@ from .binding import (  # noqa: F401
     EPILOGUE_NONE, EPILOGUE_RELU,
     BF16, F32, LAYOUT_LHS_K_MAJOR, LAYOUT_RHS_K_CONTIGUOUS, DotDims, GspmdError, Mesh, Sharding, ShardBuf,
     classify_dot, dot_workspace_bytes, grouped_dot, library_path, load_library,
-    infer_out_sharding, local_dot, plan_dot, reduce_partials, shard_assemble, shard_bounds, shard_extract,
+    infer_out_sharding, local_dot, plan_dot, reduce_partials, reshard, reshard_workspace_bytes, shard_assemble, shard_bounds, shard_extract,
     status_string, EXPORTED_SYMBOLS,
 )

@@ -14,7 +14,7 @@ LAYOUT_LHS_K_MAJOR, LAYOUT_RHS_K_CONTIGUOUS = 1, 2
 EXPORTED_SYMBOLS = (
     "gspmd_status_string", "gspmd_shard_bounds", "gspmd_classify_dot", "gspmd_dot_workspace_bytes",
     "gspmd_local_dot", "gspmd_grouped_dot", "gspmd_reduce_partials", "gspmd_shard_extract",
-    "gspmd_shard_assemble", "gspmd_plan_dot", "gspmd_infer_out_sharding",
+    "gspmd_shard_assemble", "gspmd_plan_dot", "gspmd_infer_out_sharding", "gspmd_reshard_workspace_bytes", "gspmd_reshard",
 )
 
 
@@ -77,6 +77,8 @@ def load_library():
     lib.gspmd_shard_extract.argtypes = [pm, ps, C.c_int64, C.c_void_p, pb, C.c_uint32, C.c_void_p]
     lib.gspmd_shard_assemble.argtypes = [pm, ps, C.c_int64, pb, C.c_void_p, C.c_void_p]
     lib.gspmd_infer_out_sharding.argtypes = [pm, pd, ps, ps, pi32, pi64, pi32]
+    lib.gspmd_reshard_workspace_bytes.argtypes = [pm, pi64]
+    lib.gspmd_reshard.argtypes = [pm, ps, pb, ps, pb, C.c_void_p, C.c_int64, C.c_void_p]
     lib.gspmd_plan_dot.argtypes = [pm, pd, ps, ps, ps, C.c_int64, C.c_int64, C.c_int64, C.c_int64, pi64,
                                    C.POINTER(_CGemmDesc), C.c_int64, pi64]
     for name in EXPORTED_SYMBOLS[1:]:
@@ -253,6 +255,22 @@ def grouped_dot(mesh: Mesh, dims: DotDims, lhs_shards: Sequence[ShardBuf], lhs_s
     _check(load_library().gspmd_grouped_dot(C.byref(m), C.byref(d), _bufs(lhs_shards), C.byref(a), _bufs(rhs_shards), C.byref(b),
                                             _bufs(out_shards), C.byref(o), _fill(lhs_fill), int(epilogue),
                                             C.c_void_p(workspace), int(workspace_bytes), C.c_void_p(stream)), "gspmd_grouped_dot")
+
+
+def reshard_workspace_bytes(mesh: Mesh) -> int:
+    m, n = mesh._c(), C.c_int64(0)
+    _check(load_library().gspmd_reshard_workspace_bytes(C.byref(m), C.byref(n)), "gspmd_reshard_workspace_bytes")
+    return n.value
+
+
+def reshard(mesh: Mesh, src_sh: Sharding, src_shards: Sequence[ShardBuf], dst_sh: Sharding, dst_shards: Sequence[ShardBuf],
+            workspace: int = 0, workspace_bytes: int = 0, stream: int = 0) -> None:
+    P = mesh.n_partitions
+    if not (len(src_shards) == len(dst_shards) == P):
+        raise ValueError("one shard buffer per partition is required")
+    m, a, b = mesh._c(), src_sh._c(), dst_sh._c()
+    _check(load_library().gspmd_reshard(C.byref(m), C.byref(a), _bufs(src_shards), C.byref(b), _bufs(dst_shards),
+                                        C.c_void_p(workspace), int(workspace_bytes), C.c_void_p(stream)), "gspmd_reshard")
 
 
 def reduce_partials(partials: Sequence[int], n_elems: int, out: int, out_dtype: int, stream: int = 0) -> None:

@@ -555,4 +555,137 @@ int32_t gspmd_shard_assemble(const gspmd_mesh* mesh, const gspmd_sharding* sh, i
   return shard_copy(mesh, sh, pid, nullptr, global_data, shard, 0, false, hip_stream);
 }
 
+int32_t gspmd_reshard_workspace_bytes(const gspmd_mesh* mesh, int64_t* bytes) {
+  if (!bytes) return GSPMD_ERR_NULL;
+  int64_t P = 0;
+  const int32_t st = validate_mesh(mesh, &P);
+  if (st != GSPMD_OK) return st;
+  *bytes = 2 * round_up(P * 8, kWsAlign) + round_up(P * static_cast<int64_t>(sizeof(ReshardDesc)), kWsAlign);
+  return GSPMD_OK;
+}
+
+int32_t gspmd_reshard(const gspmd_mesh* mesh, const gspmd_sharding* src_sh, const gspmd_shard_buf* src_shards,
+                      const gspmd_sharding* dst_sh, const gspmd_shard_buf* dst_shards,
+                      void* workspace, int64_t workspace_bytes, void* hip_stream) {
+  if (!src_shards || !dst_shards) return GSPMD_ERR_NULL;
+  int64_t P = 0;
+  int32_t st = validate_mesh(mesh, &P);
+  if (st != GSPMD_OK) return st;
+  if ((st = validate_sharding(mesh, src_sh)) != GSPMD_OK || (st = validate_sharding(mesh, dst_sh)) != GSPMD_OK) return st;
+  if (src_sh->rank != dst_sh->rank) return GSPMD_ERR_BAD_SHARDING;
+  const int rank = src_sh->rank, last = rank - 1;
+  for (int i = 0; i < rank; ++i)
+    if (src_sh->global_shape[i] != dst_sh->global_shape[i]) return GSPMD_ERR_BAD_SHARDING;
+  if (P > 65535) return GSPMD_ERR_UNSUPPORTED;
+  const int32_t dtype = src_shards[0].dtype;
+  for (int64_t p = 0; p < P; ++p) {
+    if ((st = check_buf(&src_shards[p])) != GSPMD_OK || (st = check_buf(&dst_shards[p])) != GSPMD_OK) return st;
+    if (src_shards[p].dtype != dtype || dst_shards[p].dtype != dtype) return GSPMD_ERR_UNSUPPORTED;
+    if (src_shards[p].row_stride != src_shards[0].row_stride || dst_shards[p].row_stride != dst_shards[0].row_stride)
+      return GSPMD_ERR_BAD_BUFFER;
+    if (!src_shards[p].data || !dst_shards[p].data) return GSPMD_ERR_NULL;
+  }
+  int64_t need = 0;
+  if ((st = gspmd_reshard_workspace_bytes(mesh, &need)) != GSPMD_OK) return st;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kWsAlign - 1)) || workspace_bytes < need) return GSPMD_ERR_WORKSPACE;
+
+  int64_t mesh_stride[kMaxRank];
+  for (int a = mesh->rank - 1, acc = 1; a >= 0; --a) { mesh_stride[a] = acc; acc *= static_cast<int>(mesh->shape[a]); }
+  bool src_uses[kMaxRank] = {false};
+  for (int i = 0; i < rank; ++i) if (src_sh->dims_mapping[i] >= 0) src_uses[src_sh->dims_mapping[i]] = true;
+
+  // strides of the src shards (one row_stride for all) from any partition's static shape
+  Bounds sb0;
+  if ((st = shard_bounds(mesh, src_sh, 0, &sb0)) != GSPMD_OK) return st;
+  int64_t src_stride[kMaxRank];
+  src_stride[last] = 1;
+  if (rank >= 2) {
+    const int64_t rs = src_shards[0].row_stride > 0 ? src_shards[0].row_stride : sb0.shard[last];
+    if (rs < sb0.shard[last]) return GSPMD_ERR_BAD_BUFFER;
+    src_stride[rank - 2] = rs;
+    for (int i = rank - 3; i >= 0; --i) src_stride[i] = src_stride[i + 1] * sb0.shard[i + 1];
+  }
+
+  const size_t esize = dtype == GSPMD_BF16 ? 2 : 4;
+  const int vec_elems = static_cast<int>(16 / esize);
+  uintptr_t bits = 0;
+  for (int64_t p = 0; p < P; ++p) bits |= reinterpret_cast<uintptr_t>(src_shards[p].data) | reinterpret_cast<uintptr_t>(dst_shards[p].data);
+  bool vec = !(bits & 15) && sb0.shard[last] % vec_elems == 0;
+  for (int i = 0; i < last; ++i) vec = vec && src_stride[i] % vec_elems == 0;
+
+  std::vector<ReshardDesc> descs;
+  std::vector<void*> seen;
+  int64_t max_rows = 0, max_cols = 0;
+  for (int64_t p = 0; p < P; ++p) {
+    void* dst = dst_shards[p].data;
+    if (std::find(seen.begin(), seen.end(), dst) != seen.end()) continue;   // replicas sharing a buffer: fill it once
+    seen.push_back(dst);
+    Bounds db;
+    if ((st = shard_bounds(mesh, dst_sh, p, &db)) != GSPMD_OK) return st;
+    int64_t coords[kMaxRank];
+    if ((st = mesh_coords(mesh, p, coords)) != GSPMD_OK) return st;
+    ReshardDesc d;
+    std::memset(&d, 0, sizeof(d));
+    d.dst = dst;
+    d.rank = rank;
+    int64_t rows = 1, total = 1;
+    for (int i = 0; i < rank; ++i) {
+      if (db.shard[i] > INT32_MAX) return GSPMD_ERR_UNSUPPORTED;
+      d.shard[i] = static_cast<int32_t>(db.shard[i]);
+      d.valid[i] = static_cast<int32_t>(db.valid[i]);
+      d.dst_off[i] = db.offset[i];
+      d.src_per[i] = std::max<int64_t>(sb0.shard[i], 1);
+      d.src_stride[i] = src_stride[i];
+      const int a = src_sh->dims_mapping[i];
+      d.pos_stride[i] = a >= 0 ? mesh_stride[a] : 0;
+      if (i < last) rows *= db.shard[i];
+      total *= db.shard[i];
+    }
+    for (int a = 0; a < mesh->rank; ++a) if (!src_uses[a]) d.base_pos += coords[a] * mesh_stride[a];
+    d.dst_stride[last] = 1;
+    if (rank >= 2) {
+      const int64_t rs = dst_shards[p].row_stride > 0 ? dst_shards[p].row_stride : db.shard[last];
+      if (rs < db.shard[last]) return GSPMD_ERR_BAD_BUFFER;
+      d.dst_stride[rank - 2] = rs;
+      for (int i = rank - 3; i >= 0; --i) d.dst_stride[i] = d.dst_stride[i + 1] * db.shard[i + 1];
+    }
+    if (total == 0) continue;
+    if (rows > INT32_MAX) return GSPMD_ERR_UNSUPPORTED;
+    d.rows = static_cast<int32_t>(rows);
+    vec = vec && db.shard[last] % vec_elems == 0;
+    for (int i = 0; i < last; ++i) vec = vec && d.dst_stride[i] % vec_elems == 0;
+    max_rows = std::max(max_rows, rows);
+    max_cols = std::max<int64_t>(max_cols, db.shard[last]);
+    descs.push_back(d);
+  }
+  if (descs.empty()) return GSPMD_OK;
+
+  // workspace = [device-id tensor][src pointer per partition id][descriptors]
+  const int64_t ids_bytes = round_up(P * 8, kWsAlign);
+  std::vector<char> host(static_cast<size_t>(2 * ids_bytes + descs.size() * sizeof(ReshardDesc)), 0);
+  std::memcpy(host.data(), mesh->device_ids, static_cast<size_t>(P) * 8);
+  for (int64_t p = 0; p < P; ++p) std::memcpy(host.data() + ids_bytes + p * 8, &src_shards[p].data, 8);
+  std::memcpy(host.data() + 2 * ids_bytes, descs.data(), descs.size() * sizeof(ReshardDesc));
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (hipMemcpyAsync(workspace, host.data(), host.size(), hipMemcpyHostToDevice, stream) != hipSuccess) return GSPMD_ERR_DEVICE;
+  const char* ws = static_cast<const char*>(workspace);
+  const int64_t* d_ids = reinterpret_cast<const int64_t*>(ws);
+  const void* const* d_ptrs = reinterpret_cast<const void* const*>(ws + ids_bytes);
+  const ReshardDesc* d_descs = reinterpret_cast<const ReshardDesc*>(ws + 2 * ids_bytes);
+
+  const int v = vec ? vec_elems : 1;
+  const int64_t gx = ((max_cols + v - 1) / v + 255) / 256;
+  // about 8192 workgroups in all; each thread walks down its column of rows
+  const int64_t gy = std::min<int64_t>(max_rows, std::max<int64_t>(1, 8192 / (gx * static_cast<int64_t>(descs.size()))));
+  const dim3 block(256), grid(static_cast<unsigned>(gx), static_cast<unsigned>(gy), static_cast<unsigned>(descs.size()));
+  if (dtype == GSPMD_BF16) {
+    if (vec) hipLaunchKernelGGL((reshard_kernel<bf16_bits, 8>), grid, block, 0, stream, d_descs, d_ids, d_ptrs);
+    else hipLaunchKernelGGL((reshard_kernel<bf16_bits, 1>), grid, block, 0, stream, d_descs, d_ids, d_ptrs);
+  } else {
+    if (vec) hipLaunchKernelGGL((reshard_kernel<uint32_t, 4>), grid, block, 0, stream, d_descs, d_ids, d_ptrs);
+    else hipLaunchKernelGGL((reshard_kernel<uint32_t, 1>), grid, block, 0, stream, d_descs, d_ids, d_ptrs);
+  }
+  return hipGetLastError() == hipSuccess ? GSPMD_OK : GSPMD_ERR_DEVICE;
+}
+
 }  // extern "C"

@@ -248,4 +248,62 @@ __global__ __launch_bounds__(256) void shard_copy_kernel(CopyDesc d, const T* __
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// Resharding: gather every dst shard from the src shards that own its elements.
+// ---------------------------------------------------------------------------------------
+struct ReshardDesc {              // one per distinct dst buffer
+  void* dst;
+  int32_t rank;
+  int32_t rows;                   // product of the dst shard's static extents except the last
+  int32_t shard[kMaxRank];        // dst shard, static extents
+  int32_t valid[kMaxRank];        // dst shard, valid extents
+  int64_t dst_off[kMaxRank];      // global index of the dst shard's first element
+  int64_t dst_stride[kMaxRank];
+  int64_t src_per[kMaxRank];      // static shard size of src along each dimension
+  int64_t src_stride[kMaxRank];
+  int64_t pos_stride[kMaxRank];   // mesh-position stride of the mesh dimension src splits this dimension on (0 if none)
+  int64_t base_pos;               // mesh position contributed by the mesh dimensions src is not split on
+};
+
+// grid.x covers the last dimension in vectors of VEC elements, grid.y strides over rows, grid.z = dst buffer.
+// VEC > 1 needs every chunk boundary, offset and stride of the last dimension to be a multiple of VEC elements and
+// 16-byte / 8-byte aligned pointers (checked on the host).
+template <typename T, int VEC>
+__global__ __launch_bounds__(256) void reshard_kernel(const ReshardDesc* __restrict__ descs, const int64_t* __restrict__ ids,
+                                                      const void* const* __restrict__ src_ptrs) {
+  const ReshardDesc& d = descs[blockIdx.z];
+  const int last = d.rank - 1;
+  const int c = (blockIdx.x * blockDim.x + threadIdx.x) * VEC;
+  if (c >= d.shard[last]) return;
+  struct alignas(sizeof(T) * VEC) Vec { T v[VEC]; };
+  T* __restrict__ dst = static_cast<T*>(d.dst);
+  const int64_t gl = d.dst_off[last] + c;
+  const int64_t chunk_l = gl / d.src_per[last], local_l = gl - chunk_l * d.src_per[last];
+  for (int row = blockIdx.y; row < d.rows; row += gridDim.y) {
+    int rem = row;
+    int64_t pos = d.base_pos + chunk_l * d.pos_stride[last], so = local_l, o = c;
+    bool ok = c < d.valid[last];
+    for (int k = last - 1; k >= 0; --k) {
+      const int x = rem % d.shard[k];
+      rem /= d.shard[k];
+      const int64_t gk = d.dst_off[k] + x;
+      const int64_t chunk = gk / d.src_per[k];
+      pos += chunk * d.pos_stride[k];
+      so += (gk - chunk * d.src_per[k]) * d.src_stride[k];
+      o += x * d.dst_stride[k];
+      ok = ok && x < d.valid[k];
+    }
+    Vec v;
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) v.v[j] = T(0);
+    if (ok) {
+      const T* __restrict__ src = static_cast<const T*>(src_ptrs[ids[pos]]);
+      v = *reinterpret_cast<const Vec*>(src + so);
+#pragma unroll
+      for (int j = 0; j < VEC; ++j) if (c + j >= d.valid[last]) v.v[j] = T(0);
+    }
+    *reinterpret_cast<Vec*>(dst + o) = v;
+  }
+}
+
 }  // namespace gspmd

@@ -172,3 +172,24 @@ def test_device_calls_validate_before_touching_the_gpu():
     with pytest.raises(g.GspmdError) as e:
         g.reduce_partials([], 10, 256, g.F32)
     assert e.value.status == 10
+
+
+def test_reshard_validates_before_touching_the_gpu():
+    mesh = g.Mesh((2,), (0, 1))
+    a, b = S((8, 8), (0, -1)), S((8, 8), (-1, 0))
+    buf, f32buf = g.ShardBuf(4096, g.BF16, 0), g.ShardBuf(4096, g.F32, 0)
+    n = g.reshard_workspace_bytes(mesh)
+    assert n > 0 and n % 256 == 0
+    for args, status in [
+        ((mesh, a, [buf, buf], S((8, 9), (-1, 0)), [buf, buf], 4096, n), 3),                 # global shapes differ
+        ((mesh, a, [buf, buf], S((8, 8, 1), (-1, 0, -1)), [buf, buf], 4096, n), 3),          # ranks differ
+        ((mesh, a, [buf, f32buf], b, [buf, buf], 4096, n), 7),                               # mixed dtypes
+        ((mesh, a, [buf, buf], b, [buf, buf], 0, 0), 8),                                     # no workspace
+        ((mesh, a, [buf, buf], b, [buf, buf], 4096 + 8, n), 8),                              # misaligned workspace
+        ((mesh, a, [buf, g.ShardBuf(4096, g.BF16, 16)], b, [buf, buf], 4096, n), 10),        # src row strides differ
+        ((mesh, a, [buf, g.ShardBuf(0, g.BF16, 0)], b, [buf, buf], 4096, n), 1),             # null data
+        ((mesh, S((8, 8), (0, 0)), [buf, buf], b, [buf, buf], 4096, n), 3),                  # mesh dim used twice
+    ]:
+        with pytest.raises(g.GspmdError) as e:
+            g.reshard(*args)
+        assert e.value.status == status, args
