@@ -207,6 +207,43 @@ def main():
             others[ww.name] = entry
             del s2
             torch.cuda.empty_cache()
+        # the HBM-bound helpers: sum of the four fp32 K-partials of config 3 (public reduce call on buffers of that size),
+        # and the AllGather of BSM's M over a 4-partition mesh dimension that precedes the feed-forward einsum (Table 1)
+        def timed_call(fn, steps, warmup):
+            for _ in range(warmup):
+                fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(steps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / steps
+
+        n_el = 4096 * 8192
+        parts = [torch.randn(n_el, device=dev) for _ in range(4)]
+        red = torch.empty(n_el, device=dev)
+        ms = timed_call(lambda: g.reduce_partials([t.data_ptr() for t in parts], n_el, red.data_ptr(), g.F32, stream), 20, 3)
+        rbytes = 5 * n_el * 4
+        others["ksplit_matmul"]["reduce_alone"] = {"kernel": "reduce_partials_kernel", "ms": round(ms, 4), "algorithmic_bytes": rbytes,
+                                                   "gbs": round(rbytes / ms / 1e6, 1), "frac_of_hbm_peak": round(rbytes / ms / 1e6 / PEAK_HBM_GBS, 3)}
+        del parts, red
+        mesh4 = g.Mesh((4,), (0, 1, 2, 3))
+        shp = (8, 2048, 8192)
+        src_sh, dst_sh = g.Sharding(shp, (-1, -1, 0)), g.Sharding(shp, (-1, -1, -1))
+        srcs = [torch.randn(8 * 2048 * 2048, device=dev).to(torch.bfloat16) for _ in range(4)]
+        dst = torch.empty(8 * 2048 * 8192, dtype=torch.bfloat16, device=dev)
+        nws = g.reshard_workspace_bytes(mesh4)
+        wsr = torch.empty(nws + 256, dtype=torch.uint8, device=dev)
+        wbase = (wsr.data_ptr() + 255) // 256 * 256
+        sb, db = [g.ShardBuf.of(t, 0) for t in srcs], [g.ShardBuf.of(dst, 0)] * 4
+        ms = timed_call(lambda: g.reshard(mesh4, src_sh, sb, dst_sh, db, wbase, nws, stream), 20, 3)
+        gbytes = 2 * dst.numel() * 2
+        others["reshard_allgather_bsm"] = {"kernel": "reshard_kernel", "what": "BSM [8,2048,8192] bf16, M split 4 ways -> whole (one shared dst buffer)",
+                                           "ms": round(ms, 4), "algorithmic_bytes": gbytes, "gbs": round(gbytes / ms / 1e6, 1),
+                                           "frac_of_hbm_peak": round(gbytes / ms / 1e6 / PEAK_HBM_GBS, 3)}
+        del srcs, dst
         result["others"] = others
     print(json.dumps(result), flush=True)
 

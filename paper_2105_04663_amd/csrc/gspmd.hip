@@ -577,6 +577,9 @@ int32_t gspmd_reshard(const gspmd_mesh* mesh, const gspmd_sharding* src_sh, cons
   for (int i = 0; i < rank; ++i)
     if (src_sh->global_shape[i] != dst_sh->global_shape[i]) return GSPMD_ERR_BAD_SHARDING;
   if (P > 65535) return GSPMD_ERR_UNSUPPORTED;
+  // 32-bit index arithmetic in the kernel: a padded dimension (partitions x shard size) must fit
+  for (int i = 0; i < rank; ++i)
+    if (src_sh->global_shape[i] > (INT32_MAX >> 1)) return GSPMD_ERR_UNSUPPORTED;
   const int32_t dtype = src_shards[0].dtype;
   for (int64_t p = 0; p < P; ++p) {
     if ((st = check_buf(&src_shards[p])) != GSPMD_OK || (st = check_buf(&dst_shards[p])) != GSPMD_OK) return st;
@@ -633,15 +636,15 @@ int32_t gspmd_reshard(const gspmd_mesh* mesh, const gspmd_sharding* src_sh, cons
       if (db.shard[i] > INT32_MAX) return GSPMD_ERR_UNSUPPORTED;
       d.shard[i] = static_cast<int32_t>(db.shard[i]);
       d.valid[i] = static_cast<int32_t>(db.valid[i]);
-      d.dst_off[i] = db.offset[i];
-      d.src_per[i] = std::max<int64_t>(sb0.shard[i], 1);
+      d.dst_off[i] = static_cast<int32_t>(db.offset[i]);
+      d.src_per[i] = static_cast<int32_t>(std::max<int64_t>(sb0.shard[i], 1));
       d.src_stride[i] = src_stride[i];
       const int a = src_sh->dims_mapping[i];
-      d.pos_stride[i] = a >= 0 ? mesh_stride[a] : 0;
+      d.pos_stride[i] = a >= 0 ? static_cast<int32_t>(mesh_stride[a]) : 0;
       if (i < last) rows *= db.shard[i];
       total *= db.shard[i];
     }
-    for (int a = 0; a < mesh->rank; ++a) if (!src_uses[a]) d.base_pos += coords[a] * mesh_stride[a];
+    for (int a = 0; a < mesh->rank; ++a) if (!src_uses[a]) d.base_pos += static_cast<int32_t>(coords[a] * mesh_stride[a]);
     d.dst_stride[last] = 1;
     if (rank >= 2) {
       const int64_t rs = dst_shards[p].row_stride > 0 ? dst_shards[p].row_stride : db.shard[last];

@@ -257,17 +257,18 @@ struct ReshardDesc {              // one per distinct dst buffer
   int32_t rows;                   // product of the dst shard's static extents except the last
   int32_t shard[kMaxRank];        // dst shard, static extents
   int32_t valid[kMaxRank];        // dst shard, valid extents
-  int64_t dst_off[kMaxRank];      // global index of the dst shard's first element
+  int32_t dst_off[kMaxRank];      // global index of the dst shard's first element
+  int32_t src_per[kMaxRank];      // static shard size of src along each dimension
+  int32_t pos_stride[kMaxRank];   // mesh-position stride of the mesh dimension src splits this dimension on (0 if none)
+  int32_t base_pos;               // mesh position contributed by the mesh dimensions src is not split on
   int64_t dst_stride[kMaxRank];
-  int64_t src_per[kMaxRank];      // static shard size of src along each dimension
   int64_t src_stride[kMaxRank];
-  int64_t pos_stride[kMaxRank];   // mesh-position stride of the mesh dimension src splits this dimension on (0 if none)
-  int64_t base_pos;               // mesh position contributed by the mesh dimensions src is not split on
 };
 
 // grid.x covers the last dimension in vectors of VEC elements, grid.y strides over rows, grid.z = dst buffer.
 // VEC > 1 needs every chunk boundary, offset and stride of the last dimension to be a multiple of VEC elements and
-// 16-byte / 8-byte aligned pointers (checked on the host).
+// 16-byte aligned pointers (checked on the host).  The owner of an element changes only when a row crosses into
+// another src shard, so the src pointer (two dependent lookups) is fetched again only then.
 template <typename T, int VEC>
 __global__ __launch_bounds__(256) void reshard_kernel(const ReshardDesc* __restrict__ descs, const int64_t* __restrict__ ids,
                                                       const void* const* __restrict__ src_ptrs) {
@@ -277,27 +278,34 @@ __global__ __launch_bounds__(256) void reshard_kernel(const ReshardDesc* __restr
   if (c >= d.shard[last]) return;
   struct alignas(sizeof(T) * VEC) Vec { T v[VEC]; };
   T* __restrict__ dst = static_cast<T*>(d.dst);
-  const int64_t gl = d.dst_off[last] + c;
-  const int64_t chunk_l = gl / d.src_per[last], local_l = gl - chunk_l * d.src_per[last];
+  const uint32_t gl = static_cast<uint32_t>(d.dst_off[last]) + c;
+  const uint32_t chunk_l = gl / static_cast<uint32_t>(d.src_per[last]), local_l = gl - chunk_l * d.src_per[last];
+  const bool col_ok = c < d.valid[last];
+  int held_pos = -1;
+  const T* __restrict__ src = nullptr;
   for (int row = blockIdx.y; row < d.rows; row += gridDim.y) {
-    int rem = row;
-    int64_t pos = d.base_pos + chunk_l * d.pos_stride[last], so = local_l, o = c;
-    bool ok = c < d.valid[last];
+    uint32_t rem = row;
+    int pos = d.base_pos + static_cast<int>(chunk_l) * d.pos_stride[last];
+    int64_t so = local_l, o = c;
+    bool ok = col_ok;
     for (int k = last - 1; k >= 0; --k) {
-      const int x = rem % d.shard[k];
-      rem /= d.shard[k];
-      const int64_t gk = d.dst_off[k] + x;
-      const int64_t chunk = gk / d.src_per[k];
-      pos += chunk * d.pos_stride[k];
-      so += (gk - chunk * d.src_per[k]) * d.src_stride[k];
-      o += x * d.dst_stride[k];
-      ok = ok && x < d.valid[k];
+      const uint32_t x = rem % static_cast<uint32_t>(d.shard[k]);
+      rem /= static_cast<uint32_t>(d.shard[k]);
+      const uint32_t gk = static_cast<uint32_t>(d.dst_off[k]) + x;
+      const uint32_t chunk = gk / static_cast<uint32_t>(d.src_per[k]);
+      pos += static_cast<int>(chunk) * d.pos_stride[k];
+      so += static_cast<int64_t>(gk - chunk * d.src_per[k]) * d.src_stride[k];
+      o += static_cast<int64_t>(x) * d.dst_stride[k];
+      ok = ok && static_cast<int>(x) < d.valid[k];
     }
     Vec v;
 #pragma unroll
     for (int j = 0; j < VEC; ++j) v.v[j] = T(0);
     if (ok) {
-      const T* __restrict__ src = static_cast<const T*>(src_ptrs[ids[pos]]);
+      if (pos != held_pos) {
+        src = static_cast<const T*>(src_ptrs[ids[pos]]);
+        held_pos = pos;
+      }
       v = *reinterpret_cast<const Vec*>(src + so);
 #pragma unroll
       for (int j = 0; j < VEC; ++j) if (c + j >= d.valid[last]) v.v[j] = T(0);
