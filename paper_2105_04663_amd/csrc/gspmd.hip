@@ -26,11 +26,11 @@ int32_t check_buf(const gspmd_shard_buf* b) {
   return GSPMD_OK;
 }
 
-// Assign tile ids for tile edge (bm, bn); returns total tiles or -1 on overflow.
+// Assign tile ids for tile edge (bm, bn) over the VALID extents; returns total tiles or -1 on overflow.
 int64_t assign_tiles(std::vector<Problem>& ps, int bm, int bn) {
   int64_t t = 0;
   for (auto& p : ps) {
-    const int64_t tm = (static_cast<int64_t>(p.Ms) + bm - 1) / bm, tn = (static_cast<int64_t>(p.Ns) + bn - 1) / bn;
+    const int64_t tm = (static_cast<int64_t>(p.Mv) + bm - 1) / bm, tn = (static_cast<int64_t>(p.Nv) + bn - 1) / bn;
     p.tile_begin = static_cast<int32_t>(t);
     p.tiles_n = static_cast<int32_t>(tn);
     t += tm * tn;
@@ -45,7 +45,6 @@ bool mfma_eligible(const std::vector<Problem>& ps, int32_t in_dtype, int32_t lay
   const int32_t max_lda = (layout & GSPMD_LAYOUT_LHS_K_MAJOR) ? (1 << 24) : (1 << 22);
   const int32_t max_ldb = (layout & GSPMD_LAYOUT_RHS_K_CONTIGUOUS) ? (1 << 22) : (1 << 24);
   for (const auto& p : ps) {
-    if (p.Kv == 0) continue;
     if ((reinterpret_cast<uintptr_t>(p.A) | reinterpret_cast<uintptr_t>(p.B)) & 15) return false;
     if ((p.lda & 7) || (p.ldb & 7)) return false;
     if (p.lda > max_lda || p.ldb > max_ldb) return false;
@@ -53,35 +52,63 @@ bool mfma_eligible(const std::vector<Problem>& ps, int32_t in_dtype, int32_t lay
   return true;
 }
 
-// Upload the problem table into the workspace and launch the contraction over all tiles.
-int32_t launch_problems(std::vector<Problem>& ps, int32_t layout, int32_t in_dtype, int32_t out_dtype, int32_t epilogue,
+// Upload the launch tables into the workspace and run the contraction over all live tiles, then the zero fill of
+// what the tiles do not cover.  Output tiles cover the valid extents only (rounded up to whole tiles, the kernel
+// writes zeros inside a partly valid tile): tiles that would only write zeros are not interleaved with live ones,
+// which would leave compute units idle (workgroups are placed in order), and cost no workgroup launches.
+int32_t launch_problems(std::vector<Problem>& all, int32_t layout, int32_t in_dtype, int32_t out_dtype, int32_t epilogue,
                         void* workspace, int64_t workspace_bytes, hipStream_t stream) {
   // problems with an empty static output block write nothing
-  ps.erase(std::remove_if(ps.begin(), ps.end(), [](const Problem& p) { return p.Ms == 0 || p.Ns == 0; }), ps.end());
-  if (ps.empty()) return GSPMD_OK;
-  const int64_t table_bytes = static_cast<int64_t>(ps.size()) * sizeof(Problem);
+  all.erase(std::remove_if(all.begin(), all.end(), [](const Problem& p) { return p.Ms == 0 || p.Ns == 0; }), all.end());
+  if (all.empty()) return GSPMD_OK;
+  if (in_dtype == GSPMD_F32 && out_dtype != GSPMD_F32) return GSPMD_ERR_UNSUPPORTED;
+  std::vector<Problem> ps;
+  for (const auto& p : all) if (p.Mv > 0) ps.push_back(p);      // Mv, Nv, Kv are all zero or all positive
+  const bool mfma = mfma_eligible(ps, in_dtype, layout);
+  const int bm = mfma ? kMfmaBM : kGenTile, bn = mfma ? kMfmaBN : kGenTile;
+  const int64_t tiles = assign_tiles(ps, bm, bn);
+  if (tiles < 0) return GSPMD_ERR_UNSUPPORTED;
+  std::vector<ZeroRect> rects;
+  for (const auto& p : all) {
+    const int32_t rows_done = static_cast<int32_t>(std::min<int64_t>(p.Ms, (static_cast<int64_t>(p.Mv) + bm - 1) / bm * bm));
+    const int32_t cols_done = static_cast<int32_t>(std::min<int64_t>(p.Ns, (static_cast<int64_t>(p.Nv) + bn - 1) / bn * bn));
+    if (rows_done < p.Ms) rects.push_back(ZeroRect{p.C, p.ldc, rows_done, p.Ms, 0, p.Ns, 0});
+    if (cols_done < p.Ns && rows_done > 0) rects.push_back(ZeroRect{p.C, p.ldc, 0, rows_done, cols_done, p.Ns, 0});
+  }
+  const int64_t prob_bytes = static_cast<int64_t>(ps.size()) * sizeof(Problem);
+  const int64_t table_bytes = prob_bytes + static_cast<int64_t>(rects.size()) * sizeof(ZeroRect);
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kWsAlign - 1)) || workspace_bytes < table_bytes)
     return GSPMD_ERR_WORKSPACE;
-  if (in_dtype == GSPMD_F32 && out_dtype != GSPMD_F32) return GSPMD_ERR_UNSUPPORTED;
-  const bool mfma = mfma_eligible(ps, in_dtype, layout);
-  const int64_t tiles = mfma ? assign_tiles(ps, kMfmaBM, kMfmaBN) : assign_tiles(ps, kGenTile, kGenTile);
-  if (tiles < 0) return GSPMD_ERR_UNSUPPORTED;
-  if (hipMemcpyAsync(workspace, ps.data(), static_cast<size_t>(table_bytes), hipMemcpyHostToDevice, stream) != hipSuccess)
+  std::vector<char> host(static_cast<size_t>(table_bytes));
+  if (prob_bytes) std::memcpy(host.data(), ps.data(), static_cast<size_t>(prob_bytes));
+  if (!rects.empty()) std::memcpy(host.data() + prob_bytes, rects.data(), rects.size() * sizeof(ZeroRect));
+  if (hipMemcpyAsync(workspace, host.data(), host.size(), hipMemcpyHostToDevice, stream) != hipSuccess)
     return GSPMD_ERR_DEVICE;
   const Problem* tab = static_cast<const Problem*>(workspace);
   const int n = static_cast<int>(ps.size());
-  if (mfma) {
-    if (!launch_dot_mfma(tab, n, static_cast<int>(tiles), layout, out_dtype, epilogue, stream)) return GSPMD_ERR_DEVICE;
-    return GSPMD_OK;
+  if (tiles > 0) {
+    if (mfma) {
+      if (!launch_dot_mfma(tab, n, static_cast<int>(tiles), layout, out_dtype, epilogue, stream)) return GSPMD_ERR_DEVICE;
+    } else {
+      const dim3 grid(static_cast<unsigned>(tiles)), block(256);
+      if (in_dtype == GSPMD_F32)
+        hipLaunchKernelGGL((dot_fallback_kernel<float, float>), grid, block, 0, stream, tab, n, layout, epilogue);
+      else if (out_dtype == GSPMD_F32)
+        hipLaunchKernelGGL((dot_fallback_kernel<bf16_bits, float>), grid, block, 0, stream, tab, n, layout, epilogue);
+      else
+        hipLaunchKernelGGL((dot_fallback_kernel<bf16_bits, bf16_bits>), grid, block, 0, stream, tab, n, layout, epilogue);
+      if (hipGetLastError() != hipSuccess) return GSPMD_ERR_DEVICE;
+    }
   }
-  const dim3 grid(static_cast<unsigned>(tiles)), block(256);
-  if (in_dtype == GSPMD_F32)
-    hipLaunchKernelGGL((dot_fallback_kernel<float, float>), grid, block, 0, stream, tab, n, layout, epilogue);
-  else if (out_dtype == GSPMD_F32)
-    hipLaunchKernelGGL((dot_fallback_kernel<bf16_bits, float>), grid, block, 0, stream, tab, n, layout, epilogue);
-  else
-    hipLaunchKernelGGL((dot_fallback_kernel<bf16_bits, bf16_bits>), grid, block, 0, stream, tab, n, layout, epilogue);
-  return hipGetLastError() == hipSuccess ? GSPMD_OK : GSPMD_ERR_DEVICE;
+  if (!rects.empty()) {
+    if (rects.size() > 65535) return GSPMD_ERR_UNSUPPORTED;
+    const ZeroRect* drects = reinterpret_cast<const ZeroRect*>(static_cast<const char*>(workspace) + prob_bytes);
+    const dim3 grid(64, static_cast<unsigned>(rects.size())), block(256);
+    if (out_dtype == GSPMD_F32) hipLaunchKernelGGL((zero_rects_kernel<float>), grid, block, 0, stream, drects);
+    else hipLaunchKernelGGL((zero_rects_kernel<bf16_bits>), grid, block, 0, stream, drects);
+    if (hipGetLastError() != hipSuccess) return GSPMD_ERR_DEVICE;
+  }
+  return GSPMD_OK;
 }
 
 int32_t launch_reduce(const float* const* partials, int n_partials, int64_t rows, int64_t cols, int64_t ld_in,
@@ -353,7 +380,7 @@ int32_t gspmd_dot_workspace_bytes(const gspmd_mesh* mesh, const gspmd_dot_dims* 
     n_prob += n;
     if (pid < 0 && contracting) partial_bytes += round_up(e * 4, kWsAlign);
   }
-  *bytes = round_up(std::max<int64_t>(n_prob, 1) * static_cast<int64_t>(sizeof(Problem)), kWsAlign) + partial_bytes;
+  *bytes = round_up(std::max<int64_t>(n_prob, 1) * kTableBytesPerProblem, kWsAlign) + partial_bytes;
   return GSPMD_OK;
 }
 
@@ -420,7 +447,7 @@ int32_t gspmd_grouped_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
     if ((st = count_partition(mesh, r, lhs_sh, rhs_sh, &part_sh, p, &n, &elems[static_cast<size_t>(p)])) != GSPMD_OK) return st;
     n_bound += n;
   }
-  char* partial_base = static_cast<char*>(workspace) + round_up(std::max<int64_t>(n_bound, 1) * static_cast<int64_t>(sizeof(Problem)), kWsAlign);
+  char* partial_base = static_cast<char*>(workspace) + round_up(std::max<int64_t>(n_bound, 1) * kTableBytesPerProblem, kWsAlign);
   std::vector<float*> partial(static_cast<size_t>(P), nullptr);
   if (contracting) {
     int64_t off = 0;

@@ -112,6 +112,22 @@ __global__ __launch_bounds__(256) void dot_fallback_kernel(const Problem* __rest
   }
 }
 
+// Zero fill of the parts of static output blocks that lie in whole tiles beyond the valid extents.
+// grid.y = rectangle, grid.x strides over its elements.
+template <typename TOut>
+__global__ __launch_bounds__(256) void zero_rects_kernel(const ZeroRect* __restrict__ rects) {
+  const ZeroRect R = rects[blockIdx.y];
+  const int w = R.c1 - R.c0;
+  const int64_t total = static_cast<int64_t>(R.r1 - R.r0) * w;
+  TOut* __restrict__ C = static_cast<TOut*>(R.C);
+  for (int64_t i = blockIdx.x * static_cast<int64_t>(blockDim.x) + threadIdx.x; i < total;
+       i += static_cast<int64_t>(gridDim.x) * blockDim.x) {
+    const int64_t r = i / w;
+    const int c = static_cast<int>(i - r * w);
+    C[(R.r0 + r) * R.ldc + R.c0 + c] = TOut(0);
+  }
+}
+
 // ---------------------------------------------------------------------------------------
 // Sum of K-partials (the arithmetic of the AllReduce along a contracting mesh dimension).
 // ---------------------------------------------------------------------------------------

@@ -151,7 +151,7 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const Problem* _
   const int tile = logical_tile(blockIdx.x, gridDim.x);
   const Problem P = tab[find_problem(tab, n_prob, tile)];
   const int local = tile - P.tile_begin;
-  const int tiles_m = (P.Ms + kMfmaBM - 1) / kMfmaBM;
+  const int tiles_m = (P.Mv + kMfmaBM - 1) / kMfmaBM;   // tiles cover the valid extents; the rest of the static block is zero-filled apart
   const int band = local / (kBandRows * P.tiles_n);
   const int rows_in_band = min(kBandRows, tiles_m - band * kBandRows);
   const int in_band = local - band * kBandRows * P.tiles_n;

@@ -23,9 +23,22 @@ struct Problem {
   int32_t Ms, Ns;     // static extents of the output block (zero-filled beyond valid)
   int32_t lda, ldb, ldc;
   int32_t tile_begin; // id of this problem's first output tile in the launch
-  int32_t tiles_n;    // tile columns of this problem
+  int32_t tiles_n;    // tile columns of this problem (tiles cover the valid extents only)
 };
 static_assert(sizeof(Problem) == 64, "device layout");
+
+// A rectangle of a problem's static output block that no output tile covers (whole tile rows / columns beyond the
+// valid extents): written as 0 by a fill kernel, so that the contraction kernel is launched over live tiles only.
+struct ZeroRect {
+  void* C;
+  int32_t ldc;
+  int32_t r0, r1, c0, c1;   // rows [r0, r1) x columns [c0, c1)
+  int32_t pad;
+};
+static_assert(sizeof(ZeroRect) == 32, "device layout");
+
+// bytes of the launch tables per problem: the problem itself and at most two zero rectangles
+constexpr int64_t kTableBytesPerProblem = sizeof(Problem) + 2 * sizeof(ZeroRect);
 
 constexpr int kMaxRank = 8;
 constexpr int64_t kMaxProblems = 1 << 20;

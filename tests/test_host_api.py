@@ -103,7 +103,7 @@ def test_classification_of_the_papers_examples():
     assert g.classify_dot(MESH, ffn2, S((8, 16, 128), (0, -1, 1)), S((128, 64), (1, -1)), S((8, 16, 64), (0, -1, 1))) == (g.AXIS_LHS_FREE, g.AXIS_CONTRACTING_SCATTER)
     # its workspace holds partials with M whole: 32 partitions x [2, 16, 64] fp32
     n = g.dot_workspace_bytes(MESH, ffn2, S((8, 16, 128), (0, -1, 1)), S((128, 64), (1, -1)), S((8, 16, 64), (0, -1, 1)), -1)
-    assert n == 32 * 2 * 64 + 32 * 2 * 16 * 64 * 4      # table (up to one problem per B index) + partials
+    assert n == 32 * 2 * 128 + 32 * 2 * 16 * 64 * 4     # tables (up to one problem per B index) + partials
 
 
 @pytest.mark.parametrize("lhs,rhs,out", [
@@ -143,10 +143,10 @@ def test_size_one_mesh_dim_splits_nothing():
 def test_workspace_query():
     n_local = g.dot_workspace_bytes(MESH, MM, S((6000, 12288), (0, -1)), S((12288, 10000), (-1, 1)), S((6000, 10000), (0, 1)), 3)
     n_all = g.dot_workspace_bytes(MESH, MM, S((6000, 12288), (0, -1)), S((12288, 10000), (-1, 1)), S((6000, 10000), (0, 1)), -1)
-    assert n_local == 256 and n_all == 32 * 64
+    assert n_local == 256 and n_all == 32 * 128      # 128 bytes of launch tables per GEMM problem
     mesh = g.Mesh((4,), (0, 1, 2, 3))
     n_k = g.dot_workspace_bytes(mesh, MM, S((4096, 16384), (-1, 0)), S((16384, 8192), (0, -1)), S((4096, 8192), (-1, -1)), -1)
-    assert n_k == 256 + 4 * 4096 * 8192 * 4     # table + four fp32 partials
+    assert n_k == 512 + 4 * 4096 * 8192 * 4     # tables + four fp32 partials
 
 
 def test_device_calls_validate_before_touching_the_gpu():
