@@ -51,7 +51,8 @@ typedef enum { GSPMD_F32 = 0, GSPMD_BF16 = 1 } gspmd_dtype;
 /* How a mesh dimension is used by one Dot (Section 3.2 taxonomy applied per mesh dimension,
  * the cases matched recursively in Section 4.4). */
 typedef enum {
-  GSPMD_AXIS_UNUSED = 0,      /* no operand or output dimension is split on it (replicated) */
+  GSPMD_AXIS_UNUSED = 0,      /* no operand or output dimension is split on it (replicated); always the class of a
+                                 mesh dimension of size 1, which splits nothing whatever is mapped to it */
   GSPMD_AXIS_BATCH = 1,       /* the same batch dimension of lhs, rhs and out */
   GSPMD_AXIS_LHS_FREE = 2,    /* a non-contracting lhs dimension and the matching out dimension */
   GSPMD_AXIS_RHS_FREE = 3,    /* a non-contracting rhs dimension and the matching out dimension */

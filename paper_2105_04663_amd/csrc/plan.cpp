@@ -147,7 +147,9 @@ int32_t analyse_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
   for (int a = 0; a < mesh->rank; ++a) {
     const int ld = find_axis_dim(lhs_sh, a), rd = find_axis_dim(rhs_sh, a), od = find_axis_dim(out_sh, a);
     int cls = -1;
-    if (ld < 0 && rd < 0 && od < 0) {
+    // A mesh dimension of size 1 splits nothing: whatever is mapped to it is whole (in particular a contracting
+    // dimension mapped to it needs no partial sums).
+    if (mesh->shape[a] == 1 || (ld < 0 && rd < 0 && od < 0)) {
       cls = GSPMD_AXIS_UNUSED;
     } else if (ld >= 0 && rd >= 0 && od >= 0) {
       const int bi = index_of(r->lhs_batch, nb, ld);
@@ -165,8 +167,6 @@ int32_t analyse_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
       const int ci = index_of(r->lhs_contract, nc, ld);
       if (ci >= 0 && r->rhs_contract[ci] == rd) cls = GSPMD_AXIS_CONTRACTING;
     }
-    // A mesh dimension of size 1 splits nothing: whatever is mapped to it is whole.
-    if (cls < 0 && mesh->shape[a] == 1) cls = GSPMD_AXIS_UNUSED;
     if (cls < 0) return GSPMD_ERR_NEEDS_RESHARD;
     if (axis_class) axis_class[a] = cls;
   }

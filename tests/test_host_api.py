@@ -137,7 +137,10 @@ def test_size_one_mesh_dim_splits_nothing():
     mesh = g.Mesh((1, 1), (0,))
     ffn = g.DotDims((), (), (2,), (0,))
     # config 2: one device's share, expressed on a (1,1) mesh
-    assert g.classify_dot(mesh, ffn, S((8, 16, 64), (0, -1, -1)), S((64, 128), (-1, 1)), S((8, 16, 128), (0, -1, 1))) == (g.AXIS_LHS_FREE, g.AXIS_RHS_FREE)
+    assert g.classify_dot(mesh, ffn, S((8, 16, 64), (0, -1, -1)), S((64, 128), (-1, 1)), S((8, 16, 128), (0, -1, 1))) == (g.AXIS_UNUSED, g.AXIS_UNUSED)
+    # a contracting dimension mapped to a size-1 mesh dimension needs no partial sums (and no partial buffers)
+    assert g.classify_dot(mesh, ffn, S((8, 16, 64), (0, -1, 1)), S((64, 128), (1, -1)), S((8, 16, 128), (0, -1, -1))) == (g.AXIS_UNUSED, g.AXIS_UNUSED)
+    assert g.dot_workspace_bytes(mesh, ffn, S((8, 16, 64), (0, -1, 1)), S((64, 128), (1, -1)), S((8, 16, 128), (0, -1, -1)), -1) == 1024
 
 
 def test_workspace_query():
