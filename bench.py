@@ -146,6 +146,15 @@ def main():
     lhs_np, rhs_np = w.draw_lhs(), w.draw_rhs()
     st = Staged(w, lhs_np, rhs_np)
     wall_ms, ev_ms = timed(st, args.steps, args.warmup)
+    # per-launch durations of a second pass (one event pair per step): median and minimum beside the mean
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    evs[0].record()
+    for i in range(args.steps):
+        st.step()
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    per = sorted(evs[i].elapsed_time(evs[i + 1]) for i in range(args.steps))
+    prop = torch.cuda.get_device_properties(0)
     flops = w.useful_flops()
     tflops = flops / (wall_ms * 1e-3) / 1e12
     kern_tflops = flops / (ev_ms * 1e-3) / 1e12
@@ -159,7 +168,11 @@ def main():
         "roofline": {"bound": "mfma", "achieved": round(kern_tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(kern_tflops / PEAK_BF16_TFLOPS, 4), "traffic": FFN_TRAFFIC_BYTES,
                      "algorithmic_bytes": 16384 * 8192 * 2 + 8192 * 8192 * 2 + 16384 * 8192 * 2,
-                     "kernel": "dot_mfma_kernel", "kernel_ms": round(ev_ms, 4)},
+                     "kernel": "dot_mfma_kernel", "kernel_ms": round(ev_ms, 4),
+                     "kernel_ms_median": round(per[len(per) // 2], 4), "kernel_ms_min": round(per[0], 4)},
+        "device": {"name": prop.name, "compute_units": prop.multi_processor_count, "hbm_gib": round(prop.total_memory / 2 ** 30, 1),
+                   "max_clock_mhz": getattr(prop, "clock_rate", 0) // 1000 or None,
+                   "peak_used": "256 CU x 4096 flop/clk x 2.4 GHz = 2516.6 TFLOP/s dense bf16; HBM 8 TB/s"},
     }
 
     # ------------------------------------------------------------------ CPU oracle on a row sample
