@@ -404,6 +404,29 @@ def test_relu_is_applied_after_the_sum_of_partials():
     assert e.value.status == 7
 
 
+@pytest.mark.parametrize("scatter", [False, True])
+def test_attention_projection_einsums_small(scatter):
+    # BSM,MND->BSND: 5 heads over Y = 2 (shards of 3, the last holds 2), B = 3 over X = 2; rhs has two free dims
+    w = wl.attn_qkv(B=3, S=50, M=200, N=5, D=24, X=2, Y=2)
+    lhs, rhs = wl.draw_normal_bf16(1, w.lhs_shape), wl.draw_normal_bf16(2, w.rhs_shape, 0.05)
+    st = Staged(w, lhs, rhs, row_align=8)
+    assert g.classify_dot(st.mesh, st.dims, st.lhs_sh, st.rhs_sh, st.out_sh) == (g.AXIS_LHS_FREE, g.AXIS_RHS_FREE)
+    st.run_grouped()
+    ref = oracle_global(w, lhs, rhs)
+    compare_all_shards(st, w, ref)
+    check(st.assemble(), ref, what="BSND reassembled")
+    # BSND,NDM->BSM: two contracting dims, the outer one (heads) split unevenly over Y; sum over Y, optionally scattered
+    w = wl.attn_out(B=3, S=50, N=5, D=24, M=264, X=2, Y=2, scatter=scatter)
+    lhs, rhs = wl.draw_normal_bf16(3, w.lhs_shape), wl.draw_normal_bf16(4, w.rhs_shape, 0.05)
+    st = Staged(w, lhs, rhs, row_align=8)
+    want_cls = (g.AXIS_LHS_FREE, g.AXIS_CONTRACTING_SCATTER if scatter else g.AXIS_CONTRACTING)
+    assert g.classify_dot(st.mesh, st.dims, st.lhs_sh, st.rhs_sh, st.out_sh) == want_cls
+    st.run_grouped()
+    ref = oracle_global(w, lhs, rhs)
+    compare_all_shards(st, w, ref)
+    check(st.assemble(), ref, what="BSM reassembled")
+
+
 def test_second_layer_einsums_small():
     # BSH,HM->BSM with H split over 4 partitions (uneven: 1000/4 = 250, rows padded to 256) and bf16 output of the sum
     w = wl.ffn_second(B=3, S=70, H=1000, M=264, Y=4)

@@ -281,5 +281,28 @@ def ffn_dgrad(B: int = 8, S: int = 2048, H: int = 8192, M: int = 8192, X: int = 
         lhs_map=(0, -1, 1), rhs_map=(-1, 1), out_map=(0, -1, -1), einsum="BSH,MH->BSM")
 
 
+def attn_qkv(B: int = 8, S: int = 2048, M: int = 8192, N: int = 32, D: int = 256, X: int = 1, Y: int = 1) -> DotWorkload:
+    """Attention input projection BSM,MND->BSND (Table 1: W_Q, W_K, W_V of shape MND): B split over X, the heads N over
+    Y; the rhs has two non-contracting dimensions.  Defaults are one device's share (N = 128 heads / 4)."""
+    return DotWorkload(
+        name="attn_bsm_mnd", cfg=11, dtype="bf16", out_dtype="bf16",
+        lhs_shape=(B, S, M), rhs_shape=(M, N, D),
+        lhs_batch=(), rhs_batch=(), lhs_contract=(2,), rhs_contract=(0,),
+        mesh_shape=(X, Y), device_ids=_ids(X * Y),
+        lhs_map=(0, -1, -1), rhs_map=(-1, 1, -1), out_map=(0, -1, 1, -1), einsum="BSM,MND->BSND")
+
+
+def attn_out(B: int = 8, S: int = 2048, N: int = 32, D: int = 256, M: int = 8192, X: int = 1, Y: int = 1,
+             scatter: bool = False) -> DotWorkload:
+    """Attention output projection BSND,NDM->BSM (Table 1: W_O of shape NDM): two contracting dimensions, the heads N
+    split over Y, so every partition holds a partial BSM (AllReduce, or ReduceScatter with M split over Y as well)."""
+    return DotWorkload(
+        name="attn_bsnd_ndm", cfg=12, dtype="bf16", out_dtype="bf16",
+        lhs_shape=(B, S, N, D), rhs_shape=(N, D, M),
+        lhs_batch=(), rhs_batch=(), lhs_contract=(2, 3), rhs_contract=(0, 1),
+        mesh_shape=(X, Y), device_ids=_ids(X * Y),
+        lhs_map=(0, -1, 1, -1), rhs_map=(1, -1, -1), out_map=(0, -1, 1 if scatter else -1), einsum="BSND,NDM->BSM")
+
+
 def all_configs() -> List[DotWorkload]:
     return [tiny_1d(), ffn(), ksplit(), moe(), mesh2d()]
