@@ -15,11 +15,20 @@ badly: measured 64 % pipe efficiency with one wave starved).  16x16x32 is used r
 half the accumulator registers per flop and the chip is power-limited: a pure MFMA loop on N(0,1) data sustains
 1996 TFLOP/s with 16x16x32 and 1700 with 32x32x16 (both reach 2480 on all-zero data).
 Global->LDS tile loads (global_load_lds_dwordx4, 1 KiB per wave-instruction) are issued only from MFMA phases, one
-after every 8th MFMA and staggered by wave, so the CU's texture-address unit (about one such load per 16 cycles) sees
+after every 6th MFMA and staggered by wave, so the CU's texture-address unit (about one such load per 16 cycles) sees
 an even stream and never stalls an MFMA wave; a whole tile is loaded by the four waves of ONE group: group 0 loads
 tile 2u+4 during the MFMA phase of step u, group 1 tile 2u+5.  With five stages every load has at least one full
-phase (>= 1024 cycles) plus the slack of a read phase to land; s_waitcnt vmcnt sits right before the barrier that
-publishes the tile.
+phase (>= 1024 cycles) plus the slack of a read phase to land.
+The end of an MFMA phase is the loop's critical path (the other group's MFMAs wait at the barrier for it), so
+nothing but the barrier follows the last MFMA: the loads are all issued by MFMA 46, and the scalar bookkeeping of the
+phase (pointer advance, stage ring, loop counter, s_waitcnt vmcnt for the tile this barrier publishes) is spread, one
+instruction after each MFMA, over MFMAs 48-62; the LDS write base of the next phase is formed before the barrier that
+starts it.  This was worth 4 % over doing the bookkeeping after the last MFMA.  The bookkeeping passes values through SCC
+(compare -> select, add -> add with carry), so only MFMAs may be interleaved with it, never a tile load (whose
+s_add_u32 of M0 overwrites SCC); tests/test_mainloop_schedule.py executes the scalar stream of every macro in an
+interpreter and checks pointers, LDS destinations and barrier counts against closed forms.
+Arriving at the barrier a few MFMAs early instead (so that the other group's first MFMAs overlap this group's last)
+is slower by 4-6 %: two waves issuing MFMAs on one SIMD at once is what the alternation exists to avoid.
 
 Operand layouts.  Each operand's LDS tile keeps the operand's own memory order, so there are two tile formats.
 K-major (rows of 256 m resp. n): the part of tile t is [32 k][256 columns]; a fragment is two ds_read_b64_tr_b16,
@@ -143,9 +152,16 @@ def advance():
             "s_add_u32 s42, s42, s51", "s_addc_u32 s43, s43, 0"] + step_stage("s52", 2)
 
 
-def mfma_phase(w):
-    load_pos = {8 * j + 2 * w: j for j in range(8)}
-    out = ["s_add_u32 s49, s44, s52"]
+def mfma_phase(w, tail):
+    """64 MFMAs.  Tile loads go after MFMAs 6j + (wave-dependent offset), all issued by MFMA 46.  The pointer / stage
+    bookkeeping and `tail` (loop counter, wait) follow, one scalar instruction after each MFMA from 48 on, so that
+    nothing but the barrier comes after the last MFMA.  Only MFMAs are interleaved with the bookkeeping: it passes
+    values through SCC (compare -> select, add -> add-with-carry), which the s_add_u32 of a tile load would overwrite."""
+    load_pos = {6 * j + (6 * w) // 4: j for j in range(8)}
+    assert len(load_pos) == 8 and max(load_pos) < 48
+    out = []
+    adv = advance() + tail
+    assert len(adv) <= 15
     i = 0
     for q in range(2):
         for bm in range(8):
@@ -153,25 +169,26 @@ def mfma_phase(w):
                 out.append(f"v_mfma_f32_16x16x32_bf16 {acc(bm, bn)}, {fb(q, bn)}, {fa(q, bm)}, {acc(bm, bn)}")
                 if i in load_pos:
                     out += load(load_pos[i])
+                if 48 <= i < 63 and adv:
+                    out.append(adv.pop(0))
                 i += 1
-    out += advance()
+    assert not adv
     return out
 
 
 def group0(w, layout):
     """Waves 0-3: read phase of K step u, barrier, MFMA phase of u (loading tile 2u+4), barrier."""
-    s = ["L0_top_%=:"] + mem_phase(layout) + ["s_waitcnt lgkmcnt(0)", "s_barrier"]
-    s += mfma_phase(w)
-    s += ["s_waitcnt vmcnt(8)", "s_barrier",
-          "s_sub_u32 s45, s45, 1", "s_cmp_lg_u32 s45, 0", "s_cbranch_scc1 L0_top_%=", "s_nop 15", "s_nop 15"]
+    s = ["L0_top_%=:"] + mem_phase(layout) + ["s_add_u32 s49, s44, s52", "s_waitcnt lgkmcnt(0)", "s_barrier"]
+    s += mfma_phase(w, ["s_sub_u32 s45, s45, 1", "s_waitcnt vmcnt(8)"])
+    s += ["s_barrier", "s_cmp_lg_u32 s45, 0", "s_cbranch_scc1 L0_top_%=", "s_nop 15", "s_nop 15"]
     return s
 
 
 def group1(w, layout):
     """Waves 4-7: one phase behind group 0 (extra barrier first); loads tile 2u+5 in its MFMA phase."""
-    s = ["s_barrier", "L1_top_%=:"] + mem_phase(layout) + ["s_waitcnt vmcnt(0) lgkmcnt(0)", "s_barrier"]
-    s += mfma_phase(w)
-    s += ["s_sub_u32 s45, s45, 1", "s_cmp_lg_u32 s45, 0", "s_cbranch_scc0 L1_end_%=",
+    s = ["s_barrier", "L1_top_%=:"] + mem_phase(layout) + ["s_add_u32 s49, s44, s52", "s_waitcnt vmcnt(0) lgkmcnt(0)", "s_barrier"]
+    s += mfma_phase(w, ["s_sub_u32 s45, s45, 1"])
+    s += ["s_cmp_lg_u32 s45, 0", "s_cbranch_scc0 L1_end_%=",
           "s_barrier", "s_branch L1_top_%=", "L1_end_%=:", "s_nop 15", "s_nop 15"]
     return s
 
