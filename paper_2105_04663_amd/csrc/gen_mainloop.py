@@ -152,12 +152,16 @@ def advance():
             "s_add_u32 s42, s42, s51", "s_addc_u32 s43, s43, 0"] + step_stage("s52", 2)
 
 
-def mfma_phase(w, tail):
+LOAD_STRIDE = (int(__import__("os").environ.get("GSPMD_LS0", "6")), int(__import__("os").environ.get("GSPMD_LS1", "6")))
+
+
+def mfma_phase(w, tail, grp=0):
     """64 MFMAs.  Tile loads go after MFMAs 6j + (wave-dependent offset), all issued by MFMA 46.  The pointer / stage
     bookkeeping and `tail` (loop counter, wait) follow, one scalar instruction after each MFMA from 48 on, so that
     nothing but the barrier comes after the last MFMA.  Only MFMAs are interleaved with the bookkeeping: it passes
     values through SCC (compare -> select, add -> add-with-carry), which the s_add_u32 of a tile load would overwrite."""
-    load_pos = {6 * j + (6 * w) // 4: j for j in range(8)}
+    st = LOAD_STRIDE[grp]
+    load_pos = {st * j + (st * w) // 4: j for j in range(8)}
     assert len(load_pos) == 8 and max(load_pos) < 48
     out = []
     adv = advance() + tail
@@ -187,7 +191,7 @@ def group0(w, layout):
 def group1(w, layout):
     """Waves 4-7: one phase behind group 0 (extra barrier first); loads tile 2u+5 in its MFMA phase."""
     s = ["s_barrier", "L1_top_%=:"] + mem_phase(layout) + ["s_add_u32 s49, s44, s52", "s_waitcnt vmcnt(0) lgkmcnt(0)", "s_barrier"]
-    s += mfma_phase(w, ["s_sub_u32 s45, s45, 1"])
+    s += mfma_phase(w, ["s_sub_u32 s45, s45, 1"], 1)
     s += ["s_cmp_lg_u32 s45, 0", "s_cbranch_scc0 L1_end_%=",
           "s_barrier", "s_branch L1_top_%=", "L1_end_%=:", "s_nop 15", "s_nop 15"]
     return s
