@@ -169,3 +169,18 @@ def test_input_gradient_full_size():
     out = out_tensor(st, 0).view(8, 2048, 8192)
     got = to_f64(out[:, torch.from_numpy(s_idx).cuda(), :].contiguous())
     check(got, ref, "BSH,MH->BSM")
+
+
+def test_very_long_contraction_is_exact():
+    # K = 2^19: 8192 K steps of one 300 x 264 problem (2 x 2 tiles); operands in {-1, 0, 1} keep every fp32 partial sum
+    # exact, so the result must equal the oracle bit for bit (tile pointers advance over 275 MB of lhs and rhs)
+    M, K, N = 300, 1 << 19, 264
+    rng = np.random.default_rng(19)
+    lhs = wl.f32_to_bf16_bits(rng.integers(-1, 2, size=(M, K)).astype(np.float32))
+    rhs = wl.f32_to_bf16_bits(rng.integers(-1, 2, size=(K, N)).astype(np.float32))
+    w = wl.mesh2d(M=M, K=K, N=N, X=1, Y=1, cfg=7)
+    st = Staged(w, lhs, rhs, row_align=8, out_dtype="f32")
+    st.run_grouped()
+    ref = od.dot_general(wl.bf16_bits_to_f64(lhs), wl.bf16_bits_to_f64(rhs), (), (), (1,), (0,))
+    got = st.out_shard(0)
+    assert np.array_equal(got, ref)
