@@ -258,6 +258,35 @@ int32_t gspmd_reshard(const gspmd_mesh* mesh,
                       const gspmd_sharding* dst_sh, const gspmd_shard_buf* dst_shards,
                       void* workspace, int64_t workspace_bytes, void* hip_stream);
 
+/* The operand shardings a Dot with output sharding `out_sh` can consume without communication, chosen as close to
+ * the given ones as the output allows (the resharding decision of Section 4.5 for one Dot): per mesh dimension, an
+ * operand dimension keeps its split if the output (or, for a contracting pair, the other operand) is split alike,
+ * receives the split its out dimension has, and is made whole otherwise.  A mesh dimension that splits the same
+ * contracting pair in both operands is kept (partial sums, possibly scattered).  lhs_mapping / rhs_mapping: host arrays
+ * of lhs_sh->rank / rhs_sh->rank entries.  Shardings that are already compatible come back unchanged.  Pure host work. */
+int32_t gspmd_compatible_operand_shardings(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
+                                           const gspmd_sharding* lhs_sh, const gspmd_sharding* rhs_sh,
+                                           const gspmd_sharding* out_sh,
+                                           int32_t* lhs_mapping, int32_t* rhs_mapping);
+
+/* Bytes of device workspace gspmd_resharded_dot needs (temporaries for the resharded operands of `in_dtype`, the tables
+ * of the two reshards and the workspace of the grouped Dot).  Pure host work. */
+int32_t gspmd_resharded_dot_workspace_bytes(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
+                                            const gspmd_sharding* lhs_sh, const gspmd_sharding* rhs_sh,
+                                            const gspmd_sharding* out_sh, int32_t in_dtype, int64_t* bytes);
+
+/* gspmd_grouped_dot for ANY operand shardings: operands whose sharding the Dot cannot consume as it is are first
+ * rewritten (gspmd_reshard, into temporaries inside the workspace, rows padded to 8 elements) to the shardings
+ * gspmd_compatible_operand_shardings names -- the AllGather / AllToAll / DynamicSlice a partitioner would insert in
+ * front of the Dot (Section 4.5) -- then the grouped Dot runs on them; GSPMD_ERR_NEEDS_RESHARD is never returned.
+ * Arguments as for gspmd_grouped_dot; lhs_fill counts refer to the global lhs as there. */
+int32_t gspmd_resharded_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
+                            const gspmd_shard_buf* lhs_shards, const gspmd_sharding* lhs_sh,
+                            const gspmd_shard_buf* rhs_shards, const gspmd_sharding* rhs_sh,
+                            const gspmd_shard_buf* out_shards, const gspmd_sharding* out_sh,
+                            const int64_t* lhs_fill, int32_t epilogue,
+                            void* workspace, int64_t workspace_bytes, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -15,6 +15,7 @@ EXPORTED_SYMBOLS = (
     "gspmd_status_string", "gspmd_shard_bounds", "gspmd_classify_dot", "gspmd_dot_workspace_bytes",
     "gspmd_local_dot", "gspmd_grouped_dot", "gspmd_reduce_partials", "gspmd_shard_extract",
     "gspmd_shard_assemble", "gspmd_plan_dot", "gspmd_infer_out_sharding", "gspmd_reshard_workspace_bytes", "gspmd_reshard",
+    "gspmd_compatible_operand_shardings", "gspmd_resharded_dot_workspace_bytes", "gspmd_resharded_dot",
 )
 
 
@@ -79,6 +80,9 @@ def load_library():
     lib.gspmd_infer_out_sharding.argtypes = [pm, pd, ps, ps, pi32, pi64, pi32]
     lib.gspmd_reshard_workspace_bytes.argtypes = [pm, pi64]
     lib.gspmd_reshard.argtypes = [pm, ps, pb, ps, pb, C.c_void_p, C.c_int64, C.c_void_p]
+    lib.gspmd_compatible_operand_shardings.argtypes = [pm, pd, ps, ps, ps, pi32, pi32]
+    lib.gspmd_resharded_dot_workspace_bytes.argtypes = [pm, pd, ps, ps, ps, C.c_int32, pi64]
+    lib.gspmd_resharded_dot.argtypes = [pm, pd, pb, ps, pb, ps, pb, ps, pi64, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p]
     lib.gspmd_plan_dot.argtypes = [pm, pd, ps, ps, ps, C.c_int64, C.c_int64, C.c_int64, C.c_int64, pi64,
                                    C.POINTER(_CGemmDesc), C.c_int64, pi64]
     for name in EXPORTED_SYMBOLS[1:]:
@@ -271,6 +275,37 @@ def reshard(mesh: Mesh, src_sh: Sharding, src_shards: Sequence[ShardBuf], dst_sh
     m, a, b = mesh._c(), src_sh._c(), dst_sh._c()
     _check(load_library().gspmd_reshard(C.byref(m), C.byref(a), _bufs(src_shards), C.byref(b), _bufs(dst_shards),
                                         C.c_void_p(workspace), int(workspace_bytes), C.c_void_p(stream)), "gspmd_reshard")
+
+
+def compatible_operand_shardings(mesh: Mesh, dims: DotDims, lhs_sh: Sharding, rhs_sh: Sharding, out_sh: Sharding):
+    """(lhs mapping, rhs mapping) the Dot can consume without communication under `out_sh` (host only)."""
+    m, d, a, b, o = mesh._c(), dims._c(), lhs_sh._c(), rhs_sh._c(), out_sh._c()
+    lm, rm = (C.c_int32 * max(1, a.rank))(), (C.c_int32 * max(1, b.rank))()
+    _check(load_library().gspmd_compatible_operand_shardings(C.byref(m), C.byref(d), C.byref(a), C.byref(b), C.byref(o), lm, rm),
+           "gspmd_compatible_operand_shardings")
+    return tuple(lm[i] for i in range(a.rank)), tuple(rm[i] for i in range(b.rank))
+
+
+def resharded_dot_workspace_bytes(mesh: Mesh, dims: DotDims, lhs_sh: Sharding, rhs_sh: Sharding, out_sh: Sharding,
+                                  in_dtype: int) -> int:
+    m, d, a, b, o = mesh._c(), dims._c(), lhs_sh._c(), rhs_sh._c(), out_sh._c()
+    n = C.c_int64(0)
+    _check(load_library().gspmd_resharded_dot_workspace_bytes(C.byref(m), C.byref(d), C.byref(a), C.byref(b), C.byref(o),
+                                                              int(in_dtype), C.byref(n)), "gspmd_resharded_dot_workspace_bytes")
+    return n.value
+
+
+def resharded_dot(mesh: Mesh, dims: DotDims, lhs_shards: Sequence[ShardBuf], lhs_sh: Sharding,
+                  rhs_shards: Sequence[ShardBuf], rhs_sh: Sharding, out_shards: Sequence[ShardBuf], out_sh: Sharding,
+                  lhs_fill=None, workspace: int = 0, workspace_bytes: int = 0, stream: int = 0,
+                  epilogue: int = EPILOGUE_NONE) -> None:
+    P = mesh.n_partitions
+    if not (len(lhs_shards) == len(rhs_shards) == len(out_shards) == P):
+        raise ValueError("one shard buffer per partition is required")
+    m, d, a, b, o = mesh._c(), dims._c(), lhs_sh._c(), rhs_sh._c(), out_sh._c()
+    _check(load_library().gspmd_resharded_dot(C.byref(m), C.byref(d), _bufs(lhs_shards), C.byref(a), _bufs(rhs_shards), C.byref(b),
+                                              _bufs(out_shards), C.byref(o), _fill(lhs_fill), int(epilogue),
+                                              C.c_void_p(workspace), int(workspace_bytes), C.c_void_p(stream)), "gspmd_resharded_dot")
 
 
 def reduce_partials(partials: Sequence[int], n_elems: int, out: int, out_dtype: int, stream: int = 0) -> None:

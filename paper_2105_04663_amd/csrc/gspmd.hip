@@ -718,4 +718,179 @@ int32_t gspmd_reshard(const gspmd_mesh* mesh, const gspmd_sharding* src_sh, cons
   return hipGetLastError() == hipSuccess ? GSPMD_OK : GSPMD_ERR_DEVICE;
 }
 
+namespace {
+
+// Roles of the Dot's dimensions without any sharding in play (unit mesh, unsplit tensors).
+int32_t dot_roles(const gspmd_dot_dims* dims, const gspmd_sharding* lhs_sh, const gspmd_sharding* rhs_sh,
+                  const gspmd_sharding* out_sh, DotRoles* r) {
+  const int64_t one = 1, zero = 0;
+  gspmd_mesh unit{1, &one, &zero};
+  int32_t none[kMaxRank];
+  for (int i = 0; i < kMaxRank; ++i) none[i] = -1;
+  if (!lhs_sh || !rhs_sh || !out_sh) return GSPMD_ERR_NULL;
+  if (lhs_sh->rank > kMaxRank || rhs_sh->rank > kMaxRank || out_sh->rank > kMaxRank) return GSPMD_ERR_BAD_SHARDING;
+  gspmd_sharding l{lhs_sh->rank, lhs_sh->global_shape, none}, rr{rhs_sh->rank, rhs_sh->global_shape, none},
+      o{out_sh->rank, out_sh->global_shape, none};
+  return analyse_dot(&unit, dims, &l, &rr, &o, r, nullptr);
+}
+
+int index_in(const int* list, int n, int v) {
+  for (int i = 0; i < n; ++i) if (list[i] == v) return i;
+  return -1;
+}
+
+// Static shard shape and bytes (rows padded to 8 elements) of one partition's temporary under `sh`.
+int64_t temp_shard_bytes(const gspmd_mesh* mesh, const gspmd_sharding* sh, int64_t pid, size_t esize, int64_t* row_stride) {
+  Bounds b;
+  if (shard_bounds(mesh, sh, pid, &b) != GSPMD_OK) return -1;
+  const int last = b.rank - 1;
+  const int64_t ld = round_up(std::max<int64_t>(b.shard[last], 1), 8);
+  int64_t rows = 1;
+  for (int i = 0; i < last; ++i) rows *= b.shard[i];
+  if (row_stride) *row_stride = b.rank >= 2 ? ld : 0;
+  return round_up(std::max<int64_t>(rows, 1) * ld * static_cast<int64_t>(esize), kWsAlign);
+}
+
+bool same_mapping(const gspmd_sharding* sh, const int32_t* map) {
+  for (int i = 0; i < sh->rank; ++i) if (sh->dims_mapping[i] != map[i]) return false;
+  return true;
+}
+
+// Temporaries of one resharded operand: one buffer per distinct shard position (replicas share), laid out from `base`.
+// Returns the bytes used; fills `bufs` (P entries) when base is non-null.
+int64_t layout_temps(const gspmd_mesh* mesh, const gspmd_sharding* sh, int64_t P, int32_t dtype, char* base,
+                     std::vector<gspmd_shard_buf>* bufs) {
+  const size_t esize = dtype == GSPMD_BF16 ? 2 : 4;
+  std::map<std::vector<int64_t>, int64_t> at;     // shard offset -> byte offset of its buffer
+  int64_t used = 0;
+  for (int64_t p = 0; p < P; ++p) {
+    Bounds b;
+    if (shard_bounds(mesh, sh, p, &b) != GSPMD_OK) return -1;
+    std::vector<int64_t> key(b.offset, b.offset + b.rank);
+    int64_t rs = 0;
+    const int64_t bytes = temp_shard_bytes(mesh, sh, p, esize, &rs);
+    if (bytes < 0) return -1;
+    auto it = at.find(key);
+    if (it == at.end()) {
+      it = at.emplace(key, used).first;
+      used += bytes;
+    }
+    if (bufs) (*bufs)[static_cast<size_t>(p)] = gspmd_shard_buf{base ? base + it->second : nullptr, dtype, rs};
+  }
+  return used;
+}
+
+}  // namespace
+
+int32_t gspmd_compatible_operand_shardings(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
+                                           const gspmd_sharding* lhs_sh, const gspmd_sharding* rhs_sh,
+                                           const gspmd_sharding* out_sh, int32_t* lhs_mapping, int32_t* rhs_mapping) {
+  if (!lhs_mapping || !rhs_mapping) return GSPMD_ERR_NULL;
+  int32_t st = validate_mesh(mesh, nullptr);
+  if (st != GSPMD_OK) return st;
+  if ((st = validate_sharding(mesh, lhs_sh)) != GSPMD_OK || (st = validate_sharding(mesh, rhs_sh)) != GSPMD_OK ||
+      (st = validate_sharding(mesh, out_sh)) != GSPMD_OK) return st;
+  DotRoles r;
+  if ((st = dot_roles(dims, lhs_sh, rhs_sh, out_sh, &r)) != GSPMD_OK) return st;
+  for (int i = 0; i < lhs_sh->rank; ++i) lhs_mapping[i] = -1;
+  for (int i = 0; i < rhs_sh->rank; ++i) rhs_mapping[i] = -1;
+  for (int a = 0; a < mesh->rank; ++a) {
+    if (mesh->shape[a] == 1) continue;            // splits nothing
+    int ld = -1, rd = -1, od = -1;
+    for (int i = 0; i < lhs_sh->rank; ++i) if (lhs_sh->dims_mapping[i] == a) ld = i;
+    for (int i = 0; i < rhs_sh->rank; ++i) if (rhs_sh->dims_mapping[i] == a) rd = i;
+    for (int i = 0; i < out_sh->rank; ++i) if (out_sh->dims_mapping[i] == a) od = i;
+    // a contracting pair split alike on both sides stays: partial sums (scattered if the output is split on it too)
+    const int ci = ld >= 0 ? index_in(r.lhs_contract, r.nc, ld) : -1;
+    const bool contracting = ci >= 0 && r.rhs_contract[ci] == rd;
+    if (contracting) {
+      lhs_mapping[ld] = a;
+      rhs_mapping[rd] = a;
+      continue;
+    }
+    if (od < 0) continue;                         // output whole on this mesh dimension: so are the operands
+    if (od < r.nb) {                              // batch: all three split alike
+      lhs_mapping[r.lhs_batch[od]] = a;
+      rhs_mapping[r.rhs_batch[od]] = a;
+    } else if (od < r.nb + r.nlf) {
+      lhs_mapping[r.lhs_free[od - r.nb]] = a;
+    } else {
+      rhs_mapping[r.rhs_free[od - r.nb - r.nlf]] = a;
+    }
+  }
+  return GSPMD_OK;
+}
+
+int32_t gspmd_resharded_dot_workspace_bytes(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
+                                            const gspmd_sharding* lhs_sh, const gspmd_sharding* rhs_sh,
+                                            const gspmd_sharding* out_sh, int32_t in_dtype, int64_t* bytes) {
+  if (!bytes) return GSPMD_ERR_NULL;
+  if (!is_dtype(in_dtype)) return GSPMD_ERR_UNSUPPORTED;
+  int32_t lmap[kMaxRank], rmap[kMaxRank];
+  int32_t st = gspmd_compatible_operand_shardings(mesh, dims, lhs_sh, rhs_sh, out_sh, lmap, rmap);
+  if (st != GSPMD_OK) return st;
+  int64_t P = 0;
+  if ((st = validate_mesh(mesh, &P)) != GSPMD_OK) return st;
+  const gspmd_sharding l2{lhs_sh->rank, lhs_sh->global_shape, lmap}, r2{rhs_sh->rank, rhs_sh->global_shape, rmap};
+  int64_t total = 0, n = 0;
+  if ((st = gspmd_reshard_workspace_bytes(mesh, &n)) != GSPMD_OK) return st;
+  total += 2 * n;
+  if (!same_mapping(lhs_sh, lmap)) {
+    if ((n = layout_temps(mesh, &l2, P, in_dtype, nullptr, nullptr)) < 0) return GSPMD_ERR_UNSUPPORTED;
+    total += n;
+  }
+  if (!same_mapping(rhs_sh, rmap)) {
+    if ((n = layout_temps(mesh, &r2, P, in_dtype, nullptr, nullptr)) < 0) return GSPMD_ERR_UNSUPPORTED;
+    total += n;
+  }
+  if ((st = gspmd_dot_workspace_bytes(mesh, dims, &l2, &r2, out_sh, -1, 1, &n)) != GSPMD_OK) return st;
+  *bytes = total + n;
+  return GSPMD_OK;
+}
+
+int32_t gspmd_resharded_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
+                            const gspmd_shard_buf* lhs_shards, const gspmd_sharding* lhs_sh,
+                            const gspmd_shard_buf* rhs_shards, const gspmd_sharding* rhs_sh,
+                            const gspmd_shard_buf* out_shards, const gspmd_sharding* out_sh,
+                            const int64_t* lhs_fill, int32_t epilogue,
+                            void* workspace, int64_t workspace_bytes, void* hip_stream) {
+  if (!lhs_shards || !rhs_shards || !out_shards) return GSPMD_ERR_NULL;
+  int32_t lmap[kMaxRank], rmap[kMaxRank];
+  int32_t st = gspmd_compatible_operand_shardings(mesh, dims, lhs_sh, rhs_sh, out_sh, lmap, rmap);
+  if (st != GSPMD_OK) return st;
+  int64_t P = 0;
+  if ((st = validate_mesh(mesh, &P)) != GSPMD_OK) return st;
+  if ((st = check_buf(&lhs_shards[0])) != GSPMD_OK || (st = check_buf(&rhs_shards[0])) != GSPMD_OK) return st;
+  const int32_t in_dtype = lhs_shards[0].dtype;
+  if (rhs_shards[0].dtype != in_dtype) return GSPMD_ERR_UNSUPPORTED;
+  int64_t need = 0;
+  if ((st = gspmd_resharded_dot_workspace_bytes(mesh, dims, lhs_sh, rhs_sh, out_sh, in_dtype, &need)) != GSPMD_OK) return st;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kWsAlign - 1)) || workspace_bytes < need) return GSPMD_ERR_WORKSPACE;
+  const gspmd_sharding l2{lhs_sh->rank, lhs_sh->global_shape, lmap}, r2{rhs_sh->rank, rhs_sh->global_shape, rmap};
+  char* ws = static_cast<char*>(workspace);
+  int64_t rs_bytes = 0;
+  if ((st = gspmd_reshard_workspace_bytes(mesh, &rs_bytes)) != GSPMD_OK) return st;
+  char* rs_ws[2] = {ws, ws + rs_bytes};
+  ws += 2 * rs_bytes;
+  std::vector<gspmd_shard_buf> ltmp(static_cast<size_t>(P)), rtmp(static_cast<size_t>(P));
+  const gspmd_shard_buf* luse = lhs_shards;
+  const gspmd_shard_buf* ruse = rhs_shards;
+  if (!same_mapping(lhs_sh, lmap)) {
+    const int64_t n = layout_temps(mesh, &l2, P, in_dtype, ws, &ltmp);
+    if (n < 0) return GSPMD_ERR_UNSUPPORTED;
+    ws += n;
+    if ((st = gspmd_reshard(mesh, lhs_sh, lhs_shards, &l2, ltmp.data(), rs_ws[0], rs_bytes, hip_stream)) != GSPMD_OK) return st;
+    luse = ltmp.data();
+  }
+  if (!same_mapping(rhs_sh, rmap)) {
+    const int64_t n = layout_temps(mesh, &r2, P, in_dtype, ws, &rtmp);
+    if (n < 0) return GSPMD_ERR_UNSUPPORTED;
+    ws += n;
+    if ((st = gspmd_reshard(mesh, rhs_sh, rhs_shards, &r2, rtmp.data(), rs_ws[1], rs_bytes, hip_stream)) != GSPMD_OK) return st;
+    ruse = rtmp.data();
+  }
+  const int64_t left = workspace_bytes - (ws - static_cast<char*>(workspace));
+  return gspmd_grouped_dot(mesh, dims, luse, &l2, ruse, &r2, out_shards, out_sh, lhs_fill, epilogue, ws, left, hip_stream);
+}
+
 }  // extern "C"

@@ -129,3 +129,44 @@ def test_reshard_error_paths():
         with pytest.raises(g.GspmdError) as e:
             g.reshard(*args)
         assert e.value.status == status
+
+
+RESHARDED = [
+    # lhs shape, rhs shape, dims (lb, rb, lc, rc), mesh, lhs map, rhs map, out map
+    ((300, 200), (200, 264), ((), (), (1,), (0,)), (2, 2), (0, -1), (-1, 1), (-1, 1)),        # lhs rows split, out not: AllGather
+    ((300, 200), (200, 264), ((), (), (1,), (0,)), (2, 2), (-1, 0), (-1, -1), (-1, -1)),      # K split on one side only
+    ((300, 200), (200, 264), ((), (), (1,), (0,)), (2, 2), (-1, 0), (1, -1), (0, 1)),         # K on different mesh dims; out split
+    ((300, 200), (200, 264), ((), (), (1,), (0,)), (2, 3), (0, -1), (-1, 1), (1, 0)),         # out split the other way round
+    ((301, 203), (203, 265), ((), (), (1,), (0,)), (2, 3), (-1, -1), (-1, -1), (0, 1)),       # replicated operands, split out
+    ((3, 50, 64), (64, 72), ((), (), (2,), (0,)), (2, 2), (0, -1, 1), (0, 1), (0, -1, 1)),    # Table 1 finalized: two AllGathers
+    ((3, 50, 72), (72, 64), ((), (), (2,), (0,)), (2, 2), (0, -1, 1), (1, 0), (0, -1, 1)),    # second einsum: ReduceScatter kept
+    ((5, 40, 33), (5, 33, 70), ((0,), (0,), (2,), (1,)), (2, 2), (-1, 0, -1), (1, -1, -1), (0, -1, 1)),   # batch dim: AllToAll of both
+]
+
+
+@pytest.mark.parametrize("lshape,rshape,dims,mesh_shape,lmap,rmap,omap", RESHARDED)
+@pytest.mark.parametrize("row_align", [8, 0])
+def test_resharded_dot_accepts_any_shardings(lshape, rshape, dims, mesh_shape, lmap, rmap, omap, row_align):
+    P = int(np.prod(mesh_shape))
+    ids = tuple(int(x) for x in np.random.default_rng(P).permutation(P))
+    mesh, gd = g.Mesh(mesh_shape, ids), g.DotDims(*dims)
+    lhs, rhs = wl.draw_small_int_bf16(1, lshape), wl.draw_small_int_bf16(2, rshape)
+    ref = od.dot_general(wl.bf16_bits_to_f64(lhs), wl.bf16_bits_to_f64(rhs), *dims)
+    lsh, rsh, osh = g.Sharding(lshape, lmap), g.Sharding(rshape, rmap), g.Sharding(ref.shape, omap)
+    lb = stage(mesh, lsh, to_device(lhs, "bf16"), "bf16", row_align, True)
+    rb = stage(mesh, rsh, to_device(rhs, "bf16"), "bf16", row_align, True)
+    ob = stage(mesh, osh, None, "f32", row_align, True)
+    n = g.resharded_dot_workspace_bytes(mesh, gd, lsh, rsh, osh, g.BF16)
+    ws = torch.empty(n + 256, dtype=torch.uint8, device="cuda")
+    base = (ws.data_ptr() + 255) // 256 * 256
+    g.resharded_dot(mesh, gd, [x[0] for x in lb], lsh, [x[0] for x in rb], rsh, [x[0] for x in ob], osh, None, base, n,
+                    torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    for pid in range(P):
+        _, t, ld, shard = ob[pid]
+        want = od.expected_out_shard(ref, mesh_shape, ids, omap, pid)
+        got = read_shard(t, shard, ld)
+        assert got.shape == want.shape and np.array_equal(got, want), pid
+    with pytest.raises(g.GspmdError) as e:
+        g.resharded_dot(mesh, gd, [x[0] for x in lb], lsh, [x[0] for x in rb], rsh, [x[0] for x in ob], osh, None, base, n - 256, 0)
+    assert e.value.status == 8
