@@ -208,7 +208,7 @@ def main():
     if not args.headline_only:
         others = {}
         for make in (wl.ksplit, wl.moe, wl.mesh2d, wl.ffn_second, lambda: wl.ffn_second(scatter=True), wl.moe_second, wl.ffn_wgrad,
-                     wl.ffn_dgrad):
+                     wl.ffn_dgrad, wl.moe_wgrad):
             ww = make()
             s2 = Staged(ww)
             # staging leaves the GPU idle for seconds: warm up for at least 80 ms (and 5 steps) before timing

@@ -190,10 +190,12 @@ int32_t gspmd_dot_workspace_bytes(const gspmd_mesh* mesh, const gspmd_dot_dims* 
  * GSPMD_EPILOGUE_NONE, and GSPMD_AXIS_CONTRACTING_SCATTER is GSPMD_ERR_UNSUPPORTED here (a slice of a
  * sum exists only after the exchange: use gspmd_grouped_dot).
  * epilogue: a gspmd_epilogue applied to every valid output element; padding stays 0.
- * lhs_fill (host, nullable): for an lhs with exactly one non-contracting dimension, the number
- * of occupied positions of that dimension per GLOBAL batch entry (row-major over the global
- * batch dims); rows at global position >= fill are masked and their out rows are 0
- * (capacity slots of the mixture-of-experts einsum, Section 5.4).
+ * lhs_fill (host, nullable): the number of occupied positions, per GLOBAL batch entry (row-major over the
+ * global batch dims), of the first lhs dimension that is not a batch dimension -- the capacity slots of the
+ * mixture-of-experts einsums (Section 5.4).  If that dimension is non-contracting it must be the only
+ * non-contracting lhs dimension: rows at global position >= fill are masked and their out rows are 0.  If it
+ * is contracting (the experts' weight gradient) it must be the outermost contracting dimension: positions
+ * >= fill take no part in the sum in either operand.
  * workspace: device, 256-byte aligned, >= gspmd_dot_workspace_bytes(); contents are
  * overwritten and must stay untouched until the stream has run the call. */
 int32_t gspmd_local_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,

@@ -288,7 +288,22 @@ int32_t plan_partition(const gspmd_mesh* mesh, const DotRoles& r,
   const int64_t lim = INT32_MAX;
   if (lm.inner_static > lim || ln.inner_static > lim || Ks > lim || lda > lim || ldb > lim || ldc > lim)
     return GSPMD_ERR_UNSUPPORTED;
-  if (lhs_fill && r.nlf != 1) return GSPMD_ERR_UNSUPPORTED;
+  // Fill counts apply to the first lhs dimension that is not a batch dimension (the capacity dimension of the
+  // mixture-of-experts einsums).  Non-contracting: it must be the only one (its rows are clamped).  Contracting (the
+  // experts' weight gradient): it must be the outermost contracting dimension (the valid K is clamped).
+  int fill_dim = -1;
+  bool fill_contracts = false;
+  if (lhs_fill) {
+    for (int i = 0; i < lr && fill_dim < 0; ++i) {
+      bool is_batch = false;
+      for (int j = 0; j < nb; ++j) is_batch = is_batch || r.lhs_batch[j] == i;
+      if (!is_batch) fill_dim = i;
+    }
+    if (fill_dim < 0) return GSPMD_ERR_UNSUPPORTED;
+    fill_contracts = r.lhs_contract[0] == fill_dim;
+    if (!fill_contracts && !(r.nlf == 1 && r.lhs_free[0] == fill_dim)) return GSPMD_ERR_UNSUPPORTED;
+  }
+  const int64_t k_inner = lb.shard[r.lhs_contract[0]] ? Ks / lb.shard[r.lhs_contract[0]] : 0;   // K positions per index of the outermost contracting dim
 
   // enumerate: batch entries x outer lhs-free x outer rhs-free (static extents, so that every
   // output element of the static shard is written)
@@ -340,18 +355,19 @@ int32_t plan_partition(const gspmd_mesh* mesh, const DotRoles& r,
     p.A = static_cast<const char*>(lhs->data) + oa * static_cast<int64_t>(ea);
     p.B = static_cast<const char*>(rhs->data) + obb * static_cast<int64_t>(eb);
     p.C = cbase + oc * static_cast<int64_t>(ec);
-    int64_t mv = live ? lm.inner_valid : 0;
+    int64_t mv = live ? lm.inner_valid : 0, kv = live ? Kv : 0;
     if (live && lhs_fill) {
       int64_t g = 0;   // row-major index over the GLOBAL batch dims
       for (int i = 0; i < nb; ++i) g = g * gsize[i] + (goff[i] + idx[i]);
       const int64_t f = lhs_fill[g];
       if (f < 0) return GSPMD_ERR_BAD_BUFFER;
-      const int fd = r.lhs_free[0];
-      mv = std::max<int64_t>(0, std::min<int64_t>(mv, f - lb.offset[fd]));
+      const int64_t occupied = std::max<int64_t>(0, f - lb.offset[fill_dim]);   // of this shard's positions
+      if (fill_contracts) kv = std::min<int64_t>(kv, occupied * k_inner);
+      else mv = std::min<int64_t>(mv, occupied);
     }
     p.Mv = static_cast<int32_t>(mv);
     p.Nv = static_cast<int32_t>(live ? ln.inner_valid : 0);
-    p.Kv = static_cast<int32_t>(live ? Kv : 0);
+    p.Kv = static_cast<int32_t>(kv);
     p.Ms = static_cast<int32_t>(lm.inner_static);
     p.Ns = static_cast<int32_t>(ln.inner_static);
     p.lda = static_cast<int32_t>(lda); p.ldb = static_cast<int32_t>(ldb); p.ldc = static_cast<int32_t>(ldc);

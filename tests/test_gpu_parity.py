@@ -178,6 +178,35 @@ def test_moe_fill_counts(mode, E, C, M, H, align):
         assert not got[e, fill[e]:].any()
 
 
+@pytest.mark.parametrize("mode", ["local", "grouped"])
+def test_moe_weight_gradient_fill_limits_the_contraction(mode):
+    # ECM,ECH->EMH: the capacity slots contract; slots beyond the fill count hold garbage (NaN) in BOTH operands here
+    # and must take no part in the sum.  Experts split over 2 partitions (uneven: 3 experts).
+    w = wl.moe_wgrad(E=3, C=200, M=264, H=130)
+    w.mesh_shape, w.device_ids = (2,), (1, 0)
+    fill = np.array([137, 200, 0], dtype=np.int64)
+    lhs, rhs = wl.draw_small_int_bf16(1, w.lhs_shape), wl.draw_small_int_bf16(2, w.rhs_shape)
+    for e in range(3):
+        lhs[e, fill[e]:] = 0x7FC0
+        rhs[e, fill[e]:] = 0x7FC0
+    st = Staged(w, lhs, rhs, row_align=8, out_dtype="f32")
+    assert [d["k_valid"] for d in g.plan_dot(st.mesh, st.dims, st.lhs_sh, st.rhs_sh, st.out_sh, 1, 264, 136, 136, lhs_fill=fill)] == [137, 200]
+    if mode == "local":
+        for pid in range(2):
+            st.run_local(pid, fill=fill)
+    else:
+        st.run_grouped(fill=fill)
+    a, b = widen(w, lhs), widen(w, rhs)
+    for e in range(3):          # what the empty slots hold is irrelevant: the oracle sees zeros there
+        a[e, fill[e]:] = 0.0
+        b[e, fill[e]:] = 0.0
+    ref = od.dot_general(a, b, w.lhs_batch, w.rhs_batch, w.lhs_contract, w.rhs_contract)
+    assert np.array_equal(od.dot_general(od.apply_fill(widen(w, np.where(lhs == 0x7FC0, 0, lhs).astype(np.uint16)), (0,), 1, fill),
+                                         widen(w, np.where(rhs == 0x7FC0, 0, rhs).astype(np.uint16)), w.lhs_batch, w.rhs_batch, w.lhs_contract, w.rhs_contract), ref)
+    compare_all_shards(st, w, ref, exact=True)
+    assert not st.out_shard(0)[0].any()      # expert 2 (fill 0) lives in partition 0's first slot: all zeros
+
+
 def test_moe_experts_sharded_over_mesh():
     # E split over 2 partitions (batch-partitioned mesh dim), uneven: 3 experts -> shards of 2, last valid 1
     w = wl.moe(E=3, C=200, M=128, H=264)

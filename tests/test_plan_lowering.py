@@ -148,6 +148,12 @@ def test_config_lowerings():
                    g.Sharding(w.rhs_shape, w.rhs_map), g.Sharding(w.out_shape, w.out_map), 0, lhs_fill=fill)
     assert [x["m_valid"] for x in d] == [int(f) for f in fill] and all(x["m_static"] == 1024 for x in d)
     assert [x["b_offset"] for x in d] == [e * 8192 * 32768 for e in range(4)]
+    # experts' weight gradient ECM,ECH->EMH: the fill count limits K, both operands K-major
+    w = wl.moe_wgrad()
+    fill = w.draw_fill()
+    d = g.plan_dot(g.Mesh(w.mesh_shape, w.device_ids), g.DotDims((0,), (0,), (1,), (1,)), g.Sharding(w.lhs_shape, w.lhs_map),
+                   g.Sharding(w.rhs_shape, w.rhs_map), g.Sharding(w.out_shape, w.out_map), 0, lhs_fill=fill)
+    assert [x["k_valid"] for x in d] == [int(f) for f in fill] and all(x["m_valid"] == 8192 and x["layout"] == g.LAYOUT_LHS_K_MAJOR for x in d)
     # config 5, partition 13 of the 4 x 8 mesh with rows padded to 8 elements
     w = wl.mesh2d()
     d = g.plan_dot(g.Mesh(w.mesh_shape, w.device_ids), g.DotDims((), (), (1,), (0,)), g.Sharding(w.lhs_shape, w.lhs_map),

@@ -160,10 +160,11 @@ class DotWorkload:
             k *= self.lhs_shape[d]
         out = self.out_shape
         if self.fill_range is not None:
+            # the capacity dimension (lhs dim 1) counts with its fill, whether it is a row or a contracting dimension
             if fill is None:
                 fill = self.draw_fill()
-            n = int(np.prod(out[2:]))
-            return 2.0 * float(np.sum(fill)) * n * k
+            rest = float(np.prod(out[1:])) * k / self.lhs_shape[1]
+            return 2.0 * float(np.sum(fill)) * rest
         return 2.0 * float(np.prod(out)) * k
 
 
@@ -302,6 +303,18 @@ def attn_out(B: int = 8, S: int = 2048, N: int = 32, D: int = 256, M: int = 8192
         lhs_batch=(), rhs_batch=(), lhs_contract=(2, 3), rhs_contract=(0, 1),
         mesh_shape=(X, Y), device_ids=_ids(X * Y),
         lhs_map=(0, -1, 1, -1), rhs_map=(1, -1, -1), out_map=(0, -1, 1 if scatter else -1), einsum="BSND,NDM->BSM")
+
+
+def moe_wgrad(E: int = 4, C: int = 1024, M: int = 8192, H: int = 32768) -> DotWorkload:
+    """Weight gradient of the first expert einsum, ECM,ECH->EMH: the capacity slots contract (both operands K-major),
+    so the per-expert fill count limits K instead of the rows."""
+    return DotWorkload(
+        name="moe_wgrad_ecm_ech", cfg=13, dtype="bf16", out_dtype="bf16",
+        lhs_shape=(E, C, M), rhs_shape=(E, C, H),
+        lhs_batch=(0,), rhs_batch=(0,), lhs_contract=(1,), rhs_contract=(1,),
+        mesh_shape=(1,), device_ids=(0,),
+        lhs_map=(0, -1, -1), rhs_map=(0, -1, -1), out_map=(0, -1, -1), rhs_sigma=1.0,
+        fill_range=(C // 2, C), einsum="ECM,ECH->EMH")
 
 
 def all_configs() -> List[DotWorkload]:
