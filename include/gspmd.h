@@ -17,6 +17,9 @@
  *     is the default stream) and is complete when that stream is.
  *   - Every function returns a gspmd_status and never throws, aborts or prints.
  *     Outputs are written only on GSPMD_OK.
+ *   - The library keeps no state between calls; independent calls may be made from several
+ *     host threads.  Calls that launch kernels upload small launch tables from a temporary host
+ *     buffer with a stream-ordered copy, so they must not be recorded into a HIP graph.
  *   - Tensors are row-major.  A shard buffer has the STATIC shard shape
  *     (ceil(D/n) per split dimension, Section 4.1), whatever the partition's
  *     valid length; the library reads no element at an index >= the valid
