@@ -38,6 +38,8 @@ def parse():
                     help="untimed warm-up steps (after an idle period the GPU needs about 30 launches = 50 ms to reach its steady clock)")
     ap.add_argument("--headline-only", action="store_true", help="skip the other configs and the CPU baseline")
     ap.add_argument("--cpu-rows", type=int, default=16384, help="rows of the FFN output the CPU oracle is timed on")
+    ap.add_argument("--only", default=None,
+                    help="time just one of the other workloads (by name, e.g. moe_ecm_emh) and print its entry; for profiling")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain copy of known size (shard_extract of a [16384,8192] bf16 tensor on a 1-partition "
                          "mesh: 268435456 bytes read, 268435456 written per launch) for scaling HBM byte counters")
@@ -141,6 +143,38 @@ def main():
         ev_ms = e0.elapsed_time(e1) / steps
         return wall_ms, ev_ms
 
+    other_makers = (wl.ksplit, wl.moe, wl.mesh2d, wl.ffn_second, lambda: wl.ffn_second(scatter=True), wl.moe_second, wl.ffn_wgrad,
+                    wl.ffn_dgrad, wl.moe_wgrad)
+
+    def run_other(ww):
+        s2 = Staged(ww)
+        # staging leaves the GPU idle for seconds: warm up for at least 80 ms (and 5 steps) before timing
+        t_w, n_w = time.perf_counter(), 0
+        while n_w < 5 or time.perf_counter() - t_w < 0.08:
+            s2.step()
+            n_w += 1
+            if n_w % 5 == 0:
+                torch.cuda.synchronize()
+        wall, ev = timed(s2, max(10, args.steps // 2), 2)
+        fl = ww.useful_flops(s2.fill)
+        entry = {"ms_per_step": round(wall, 4), "tflops": round(fl / (wall * 1e-3) / 1e12, 2),
+                 "pct_of_peak": round(100.0 * fl / (wall * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 2), "useful_flops": fl,
+                 "einsum": ww.einsum, "partitions": ww.n_partitions}
+        if s2.fill is not None:
+            entry["fill"] = [int(x) for x in s2.fill]
+        del s2
+        torch.cuda.empty_cache()
+        return entry
+
+    if args.only:
+        for make in other_makers:
+            ww = make()
+            if ww.name == args.only:
+                print(json.dumps({ww.name: run_other(ww)}), flush=True)
+                return
+        sys.stderr.write("bench.py: no workload named %r\n" % args.only)
+        sys.exit(2)
+
     # ------------------------------------------------------------------ headline: FFN share
     w = wl.ffn()
     lhs_np, rhs_np = w.draw_lhs(), w.draw_rhs()
@@ -207,27 +241,9 @@ def main():
     # ------------------------------------------------------------------ the other configs
     if not args.headline_only:
         others = {}
-        for make in (wl.ksplit, wl.moe, wl.mesh2d, wl.ffn_second, lambda: wl.ffn_second(scatter=True), wl.moe_second, wl.ffn_wgrad,
-                     wl.ffn_dgrad, wl.moe_wgrad):
+        for make in other_makers:
             ww = make()
-            s2 = Staged(ww)
-            # staging leaves the GPU idle for seconds: warm up for at least 80 ms (and 5 steps) before timing
-            t_w, n_w = time.perf_counter(), 0
-            while n_w < 5 or time.perf_counter() - t_w < 0.08:
-                s2.step()
-                n_w += 1
-                if n_w % 5 == 0:
-                    torch.cuda.synchronize()
-            wall, ev = timed(s2, max(10, args.steps // 2), 2)
-            fl = ww.useful_flops(s2.fill)
-            entry = {"ms_per_step": round(wall, 4), "tflops": round(fl / (wall * 1e-3) / 1e12, 2),
-                     "pct_of_peak": round(100.0 * fl / (wall * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 2), "useful_flops": fl,
-                     "einsum": ww.einsum, "partitions": ww.n_partitions}
-            if s2.fill is not None:
-                entry["fill"] = [int(x) for x in s2.fill]
-            others[ww.name] = entry
-            del s2
-            torch.cuda.empty_cache()
+            others[ww.name] = run_other(ww)
         # the HBM-bound helpers: sum of the four fp32 K-partials of config 3 (public reduce call on buffers of that size),
         # and the AllGather of BSM's M over a 4-partition mesh dimension that precedes the feed-forward einsum (Table 1)
         def timed_call(fn, steps, warmup):

@@ -103,9 +103,24 @@ int32_t launch_problems(std::vector<Problem>& all, int32_t layout, int32_t in_dt
   if (!rects.empty()) {
     if (rects.size() > 65535) return GSPMD_ERR_UNSUPPORTED;
     const ZeroRect* drects = reinterpret_cast<const ZeroRect*>(static_cast<const char*>(workspace) + prob_bytes);
-    const dim3 grid(64, static_cast<unsigned>(rects.size())), block(256);
-    if (out_dtype == GSPMD_F32) hipLaunchKernelGGL((zero_rects_kernel<float>), grid, block, 0, stream, drects);
-    else hipLaunchKernelGGL((zero_rects_kernel<bf16_bits>), grid, block, 0, stream, drects);
+    const int vec_elems = out_dtype == GSPMD_F32 ? 4 : 8;
+    bool vec = true;
+    int64_t most = 0;
+    for (const auto& r : rects) {
+      vec = vec && !(reinterpret_cast<uintptr_t>(r.C) & 15) && r.ldc % vec_elems == 0 && r.c0 % vec_elems == 0 &&
+            (r.c1 - r.c0) % vec_elems == 0;
+      most = std::max<int64_t>(most, static_cast<int64_t>(r.r1 - r.r0) * (r.c1 - r.c0));
+    }
+    const int64_t per_thread = vec ? vec_elems : 1;
+    const unsigned gx = static_cast<unsigned>(std::min<int64_t>(std::max<int64_t>((most / per_thread + 255) / 256, 1), 2048));
+    const dim3 grid(gx, static_cast<unsigned>(rects.size())), block(256);
+    if (out_dtype == GSPMD_F32) {
+      if (vec) hipLaunchKernelGGL((zero_rects_kernel<float, 4>), grid, block, 0, stream, drects);
+      else hipLaunchKernelGGL((zero_rects_kernel<float, 1>), grid, block, 0, stream, drects);
+    } else {
+      if (vec) hipLaunchKernelGGL((zero_rects_kernel<bf16_bits, 8>), grid, block, 0, stream, drects);
+      else hipLaunchKernelGGL((zero_rects_kernel<bf16_bits, 1>), grid, block, 0, stream, drects);
+    }
     if (hipGetLastError() != hipSuccess) return GSPMD_ERR_DEVICE;
   }
   return GSPMD_OK;

@@ -113,18 +113,23 @@ __global__ __launch_bounds__(256) void dot_fallback_kernel(const Problem* __rest
 }
 
 // Zero fill of the parts of static output blocks that lie in whole tiles beyond the valid extents.
-// grid.y = rectangle, grid.x strides over its elements.
-template <typename TOut>
+// grid.y = rectangle, grid.x strides over its 16-byte vectors (VEC elements; the host picks VEC = 1 unless the
+// pointers, leading dimensions, first columns and widths of all rectangles allow 16-byte stores).
+template <typename TOut, int VEC>
 __global__ __launch_bounds__(256) void zero_rects_kernel(const ZeroRect* __restrict__ rects) {
   const ZeroRect R = rects[blockIdx.y];
-  const int w = R.c1 - R.c0;
-  const int64_t total = static_cast<int64_t>(R.r1 - R.r0) * w;
+  const int wv = (R.c1 - R.c0) / VEC;
+  const int64_t total = static_cast<int64_t>(R.r1 - R.r0) * wv;
   TOut* __restrict__ C = static_cast<TOut*>(R.C);
+  struct alignas(sizeof(TOut) * VEC) Vec { TOut v[VEC]; };
+  Vec z;
+#pragma unroll
+  for (int j = 0; j < VEC; ++j) z.v[j] = TOut(0);
   for (int64_t i = blockIdx.x * static_cast<int64_t>(blockDim.x) + threadIdx.x; i < total;
        i += static_cast<int64_t>(gridDim.x) * blockDim.x) {
-    const int64_t r = i / w;
-    const int c = static_cast<int>(i - r * w);
-    C[(R.r0 + r) * R.ldc + R.c0 + c] = TOut(0);
+    const int64_t r = i / wv;
+    const int c = static_cast<int>(i - r * wv) * VEC;
+    *reinterpret_cast<Vec*>(C + (R.r0 + r) * R.ldc + R.c0 + c) = z;
   }
 }
 
