@@ -330,6 +330,28 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const Problem* _
   // ---- epilogue: lane holds, for row m, columns n .. n+3 of each 16-column block
   TOut* __restrict__ Cg = static_cast<TOut*>(P.C);
   const bool vec_ok = ((P.ldc & 3) == 0) && ((reinterpret_cast<uintptr_t>(Cg) & 15) == 0);
+  if (vec_ok && m0 + kMfmaBM <= P.Mv && n0 + kMfmaBN <= P.Nv) {
+    // tile wholly inside the valid region: no predicates; bf16 through the hardware round-to-nearest-even conversion
+    TOut* __restrict__ c0 = Cg + static_cast<int64_t>(m0 + wm * 128 + (lane & 15)) * P.ldc + n0 + wn * 64 + (lane >> 4) * 4;
+#pragma unroll
+    for (int bm = 0; bm < 8; ++bm) {
+      TOut* crow = c0 + static_cast<int64_t>(bm * 16) * P.ldc;
+#pragma unroll
+      for (int bn = 0; bn < 4; ++bn) {
+        float v[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = apply_epilogue(acc[bm][bn * 4 + j], epilogue);
+        if constexpr (sizeof(TOut) == 4) {
+          *reinterpret_cast<float4*>(crow + bn * 16) = make_float4(v[0], v[1], v[2], v[3]);
+        } else {
+          typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
+          bf16x4_t o = {static_cast<__bf16>(v[0]), static_cast<__bf16>(v[1]), static_cast<__bf16>(v[2]), static_cast<__bf16>(v[3])};
+          *reinterpret_cast<bf16x4_t*>(crow + bn * 16) = o;
+        }
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int bm = 0; bm < 8; ++bm) {
     const int m = m0 + wm * 128 + bm * 16 + (lane & 15);
