@@ -332,21 +332,40 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const Problem* _
   const bool vec_ok = ((P.ldc & 3) == 0) && ((reinterpret_cast<uintptr_t>(Cg) & 15) == 0);
   if (vec_ok && m0 + kMfmaBM <= P.Mv && n0 + kMfmaBN <= P.Nv) {
     // tile wholly inside the valid region: no predicates; bf16 through the hardware round-to-nearest-even conversion
-    TOut* __restrict__ c0 = Cg + static_cast<int64_t>(m0 + wm * 128 + (lane & 15)) * P.ldc + n0 + wn * 64 + (lane >> 4) * 4;
+    if constexpr (sizeof(TOut) == 2) {
+      // bf16: the wave's 128 x 64 block is a 128-byte line per row, but a lane holds only 8 bytes of it per 16-column
+      // block.  Stage it through the wave's own slice of LDS (free now: every wave is past the loop's last barrier;
+      // rows padded to 144 bytes against bank conflicts) and store 16 bytes per lane, 8 lanes per row: whole lines.
+      constexpr int kPitch = 144;
+      unsigned char* slice = smem + wave * (128 * kPitch);
+      typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
 #pragma unroll
-    for (int bm = 0; bm < 8; ++bm) {
-      TOut* crow = c0 + static_cast<int64_t>(bm * 16) * P.ldc;
+      for (int bm = 0; bm < 8; ++bm)
 #pragma unroll
-      for (int bn = 0; bn < 4; ++bn) {
-        float v[4];
+        for (int bn = 0; bn < 4; ++bn) {
+          float v[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) v[j] = apply_epilogue(acc[bm][bn * 4 + j], epilogue);
-        if constexpr (sizeof(TOut) == 4) {
-          *reinterpret_cast<float4*>(crow + bn * 16) = make_float4(v[0], v[1], v[2], v[3]);
-        } else {
-          typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
+          for (int j = 0; j < 4; ++j) v[j] = apply_epilogue(acc[bm][bn * 4 + j], epilogue);
           bf16x4_t o = {static_cast<__bf16>(v[0]), static_cast<__bf16>(v[1]), static_cast<__bf16>(v[2]), static_cast<__bf16>(v[3])};
-          *reinterpret_cast<bf16x4_t*>(crow + bn * 16) = o;
+          *reinterpret_cast<bf16x4_t*>(slice + (bm * 16 + (lane & 15)) * kPitch + bn * 32 + (lane >> 4) * 8) = o;
+        }
+      TOut* __restrict__ c0 = Cg + static_cast<int64_t>(m0 + wm * 128 + (lane >> 3)) * P.ldc + n0 + wn * 64 + (lane & 7) * 8;
+#pragma unroll
+      for (int p = 0; p < 16; ++p) {
+        const u32x4_t v = *reinterpret_cast<const u32x4_t*>(slice + (p * 8 + (lane >> 3)) * kPitch + (lane & 7) * 16);
+        *reinterpret_cast<u32x4_t*>(c0 + static_cast<int64_t>(p * 8) * P.ldc) = v;
+      }
+    } else {
+      TOut* __restrict__ c0 = Cg + static_cast<int64_t>(m0 + wm * 128 + (lane & 15)) * P.ldc + n0 + wn * 64 + (lane >> 4) * 4;
+#pragma unroll
+      for (int bm = 0; bm < 8; ++bm) {
+        TOut* crow = c0 + static_cast<int64_t>(bm * 16) * P.ldc;
+#pragma unroll
+        for (int bn = 0; bn < 4; ++bn) {
+          float v[4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) v[j] = apply_epilogue(acc[bm][bn * 4 + j], epilogue);
+          *reinterpret_cast<float4*>(crow + bn * 16) = make_float4(v[0], v[1], v[2], v[3]);
         }
       }
     }
