@@ -44,6 +44,9 @@ The forward einsums have a K-contiguous lhs and a K-major rhs; a weight gradient
 both K-contiguous.  One set of macros is written per combination (GSPMD_MAINLOOP_L<layout>_..., layout bit 0 = lhs
 K-major, bit 1 = rhs K-contiguous); only the read phase differs (32, 48, 24 or 40 LDS reads into the same 96 fragment
 registers).
+Partly valid tiles: when the valid rows of an output tile end inside group 1's half (rows 128-255), its waves run a
+variant (..._G1R4_..., ..._G1R6_...) that reads and multiplies only the first 4 or 6 of their 8 row blocks; the rest of
+their accumulators stays zero and is never stored.  Group 0 and the loads are unchanged.
 
 Register plan per wave: v[0:127] accumulators acc(bm, bn) = v[4*(4*bm+bn) ..+3] (bm = 16-row block 0..7 of the
 wave's 128 rows, bn = 16-column block 0..3 of its 64 columns); fragments of tile q (0/1) of the K step:
@@ -101,9 +104,9 @@ def read_addrs(layout, q):
     return out
 
 
-def ds_reads(q, layout):
+def ds_reads(q, layout, nbm=8):
     out = []
-    for bm in range(8):
+    for bm in range(nbm):
         if layout & 1:      # K-major lhs: block bm at address ^ (bm << 5), formed in one of two alternating registers
             reg = "v224" if bm == 0 else f"v{229 + (bm & 1)}"
             if bm:
@@ -125,9 +128,9 @@ def step_stage(reg, n):
     return [f"s_add_u32 {reg}, {reg}, {STAGE * n}", f"s_sub_u32 s48, {reg}, {LDS}", f"s_cmp_ge_u32 {reg}, {LDS}", f"s_cselect_b32 {reg}, s48, {reg}"]
 
 
-def mem_phase(layout):
-    out = (read_addrs(layout, 0) + ds_reads(0, layout) + step_stage("s53", 1)
-           + read_addrs(layout, 1) + ds_reads(1, layout) + step_stage("s53", 1))
+def mem_phase(layout, nbm=8):
+    out = (read_addrs(layout, 0) + ds_reads(0, layout, nbm) + step_stage("s53", 1)
+           + read_addrs(layout, 1) + ds_reads(1, layout, nbm) + step_stage("s53", 1))
     if not layout & 1:
         out += step_stage("s55", 2)
     if layout & 2:
@@ -152,28 +155,31 @@ def advance():
             "s_add_u32 s42, s42, s51", "s_addc_u32 s43, s43, 0"] + step_stage("s52", 2)
 
 
-LOAD_STRIDE = (int(__import__("os").environ.get("GSPMD_LS0", "6")), int(__import__("os").environ.get("GSPMD_LS1", "6")))
+LOAD_STRIDE = {8: 6, 6: 4, 4: 2}      # MFMAs between two tile loads of a wave, by row blocks computed
 
 
-def mfma_phase(w, tail, grp=0):
-    """64 MFMAs.  Tile loads go after MFMAs 6j + (wave-dependent offset), all issued by MFMA 46.  The pointer / stage
-    bookkeeping and `tail` (loop counter, wait) follow, one scalar instruction after each MFMA from 48 on, so that
-    nothing but the barrier comes after the last MFMA.  Only MFMAs are interleaved with the bookkeeping: it passes
-    values through SCC (compare -> select, add -> add-with-carry), which the s_add_u32 of a tile load would overwrite."""
-    st = LOAD_STRIDE[grp]
+def mfma_phase(w, tail, nbm=8):
+    """8 * nbm MFMAs (all 8 row blocks of the wave, or only the first nbm when the rest of its rows lies beyond the valid
+    extent).  Tile loads go after MFMAs stride * j + (wave-dependent offset), all issued 16 MFMAs before the end.
+    The pointer / stage bookkeeping and `tail` (loop counter, wait) follow, one scalar instruction after each MFMA,
+    so that nothing but the barrier comes after the last MFMA.  Only MFMAs are interleaved with the bookkeeping: it
+    passes values through SCC (compare -> select, add -> add-with-carry), which the s_add_u32 of a tile load would
+    overwrite."""
+    n = 8 * nbm
+    st = LOAD_STRIDE[nbm]
     load_pos = {st * j + (st * w) // 4: j for j in range(8)}
-    assert len(load_pos) == 8 and max(load_pos) < 48
+    assert len(load_pos) == 8 and max(load_pos) < n - 16
     out = []
     adv = advance() + tail
     assert len(adv) <= 15
     i = 0
     for q in range(2):
-        for bm in range(8):
+        for bm in range(nbm):
             for bn in range(4):
                 out.append(f"v_mfma_f32_16x16x32_bf16 {acc(bm, bn)}, {fb(q, bn)}, {fa(q, bm)}, {acc(bm, bn)}")
                 if i in load_pos:
                     out += load(load_pos[i])
-                if 48 <= i < 63 and adv:
+                if n - 16 <= i < n - 1 and adv:
                     out.append(adv.pop(0))
                 i += 1
     assert not adv
@@ -188,10 +194,12 @@ def group0(w, layout):
     return s
 
 
-def group1(w, layout):
-    """Waves 4-7: one phase behind group 0 (extra barrier first); loads tile 2u+5 in its MFMA phase."""
-    s = ["s_barrier", "L1_top_%=:"] + mem_phase(layout) + ["s_add_u32 s49, s44, s52", "s_waitcnt vmcnt(0) lgkmcnt(0)", "s_barrier"]
-    s += mfma_phase(w, ["s_sub_u32 s45, s45, 1"], 1)
+def group1(w, layout, nbm=8):
+    """Waves 4-7: one phase behind group 0 (extra barrier first); loads tile 2u+5 in its MFMA phase.  nbm < 8: the
+    variant for an output tile whose valid rows end inside this group's half (rows 128-255): only the first nbm
+    16-row blocks are read and multiplied."""
+    s = ["s_barrier", "L1_top_%=:"] + mem_phase(layout, nbm) + ["s_add_u32 s49, s44, s52", "s_waitcnt vmcnt(0) lgkmcnt(0)", "s_barrier"]
+    s += mfma_phase(w, ["s_sub_u32 s45, s45, 1"], nbm)
     s += ["s_cmp_lg_u32 s45, 0", "s_cbranch_scc0 L1_end_%=",
           "s_barrier", "s_branch L1_top_%=", "L1_end_%=:", "s_nop 15", "s_nop 15"]
     return s
@@ -208,6 +216,8 @@ def main():
         for w in range(4):
             out.append(macro(f"GSPMD_MAINLOOP_L{layout}_G0_W{w}", group0(w, layout)))
             out.append(macro(f"GSPMD_MAINLOOP_L{layout}_G1_W{w}", group1(w, layout)))
+            for nbm in (4, 6):
+                out.append(macro(f"GSPMD_MAINLOOP_L{layout}_G1R{nbm}_W{w}", group1(w, layout, nbm)))
     out.append(f'#define GSPMD_MAINLOOP_CLOBBERS {clob}, "s48", "s49", "s50", "s51", "m0", "scc", "vcc", "memory"')
     sys.stdout.write("\n".join(out) + "\n")
 

@@ -282,6 +282,10 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const Problem* _
         const uint32_t wrbase = lds0 + wn * 4096;
         uint32_t wstage = ((4 + wm) % kNumStages) * kStage, rstage = 0;
         uint32_t nkr = nk64;
+        // 16-row blocks of group 1's half (rows 128-255 of the tile) that hold valid rows, rounded up to 4, 6 or 8: the
+        // loop variant for fewer blocks skips the reads and MFMAs of the others (their results would never be stored)
+        const int g1_rows = min(P.Mv - m0, kMfmaBM) - 128;
+        const int g1_blocks = g1_rows <= 64 ? 4 : (g1_rows <= 96 ? 6 : 8);
         const uint32_t astep = static_cast<uint32_t>(a_tile) * 4, bstep = static_cast<uint32_t>(b_tile) * 4;   // one K step, bytes
 #define GSPMD_MAINLOOP_OPERANDS \
         : "+{v[0:15]}"(acc[0]), "+{v[16:31]}"(acc[1]), "+{v[32:47]}"(acc[2]), "+{v[48:63]}"(acc[3]), \
@@ -293,6 +297,13 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const Problem* _
         : GSPMD_MAINLOOP_CLOBBERS
         // the four waves of a group issue their tile loads after different MFMAs, so that the CU's
         // texture-address unit sees one load at a time
+#define GSPMD_RUN_G1(L, R) \
+          switch (wn) { \
+            case 0: asm volatile(GSPMD_MAINLOOP_L##L##_G1##R##_W0 GSPMD_MAINLOOP_OPERANDS); break; \
+            case 1: asm volatile(GSPMD_MAINLOOP_L##L##_G1##R##_W1 GSPMD_MAINLOOP_OPERANDS); break; \
+            case 2: asm volatile(GSPMD_MAINLOOP_L##L##_G1##R##_W2 GSPMD_MAINLOOP_OPERANDS); break; \
+            default: asm volatile(GSPMD_MAINLOOP_L##L##_G1##R##_W3 GSPMD_MAINLOOP_OPERANDS); break; \
+          }
 #define GSPMD_RUN_MAINLOOP(L) \
         if (wm == 0) { \
           switch (wn) { \
@@ -301,13 +312,12 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const Problem* _
             case 2: asm volatile(GSPMD_MAINLOOP_L##L##_G0_W2 GSPMD_MAINLOOP_OPERANDS); break; \
             default: asm volatile(GSPMD_MAINLOOP_L##L##_G0_W3 GSPMD_MAINLOOP_OPERANDS); break; \
           } \
+        } else if (g1_blocks == 8) { \
+          GSPMD_RUN_G1(L, ) \
+        } else if (g1_blocks == 6) { \
+          GSPMD_RUN_G1(L, R6) \
         } else { \
-          switch (wn) { \
-            case 0: asm volatile(GSPMD_MAINLOOP_L##L##_G1_W0 GSPMD_MAINLOOP_OPERANDS); break; \
-            case 1: asm volatile(GSPMD_MAINLOOP_L##L##_G1_W1 GSPMD_MAINLOOP_OPERANDS); break; \
-            case 2: asm volatile(GSPMD_MAINLOOP_L##L##_G1_W2 GSPMD_MAINLOOP_OPERANDS); break; \
-            default: asm volatile(GSPMD_MAINLOOP_L##L##_G1_W3 GSPMD_MAINLOOP_OPERANDS); break; \
-          } \
+          GSPMD_RUN_G1(L, R4) \
         }
         if constexpr (LAYOUT == 0) { GSPMD_RUN_MAINLOOP(0) }
         else if constexpr (LAYOUT == 1) { GSPMD_RUN_MAINLOOP(1) }

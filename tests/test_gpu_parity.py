@@ -70,6 +70,8 @@ def test_config1_tiny_fp32(mode, row_align):
 RAGGED = [  # M, K, N : several 256-tiles and ragged tails in every dimension
     (600, 200, 520), (257, 64, 255), (256, 512, 256), (1, 8, 1), (300, 1000, 264), (513, 72, 1030), (40, 4104, 24),
     # K around the kernel's 32-wide tiles and 64-wide steps: no full step, one tile + tail, odd tile counts
+    # valid rows ending inside the second half of a tile: 56, 86 and 116 rows of it (loop variants for 4, 6, 8 row blocks)
+    (440, 200, 264), (470, 200, 264), (500, 200, 264), (191, 4104, 300),
     (260, 32, 264), (260, 33, 264), (260, 95, 264), (260, 96, 264), (260, 127, 264), (260, 160, 264), (260, 321, 264),
 ]
 

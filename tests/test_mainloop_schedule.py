@@ -98,13 +98,14 @@ def initial(grp, w, nk64):
 
 
 @pytest.mark.parametrize("layout", range(4))
-@pytest.mark.parametrize("grp", [0, 1])
-def test_tile_loads_land_where_the_kernel_reads_them_and_stay_in_bounds(layout, grp):
+@pytest.mark.parametrize("grp,nbm", [(0, 8), (1, 8), (1, 6), (1, 4)])
+def test_tile_loads_land_where_the_kernel_reads_them_and_stay_in_bounds(layout, grp, nbm):
     g = generator()
     for w in range(4):
         for nk64 in (1, 2, 3, 4, 5, 9, 16):
             sg, a0, b0 = initial(grp, w, nk64)
-            lines = (g.group0 if grp == 0 else g.group1)(w, layout)
+            lines = g.group0(w, layout) if grp == 0 else g.group1(w, layout, nbm)
+            assert sum(l.startswith("v_mfma") for l in lines) == 8 * nbm
             ev, end = run(lines, sg)
             loads = [e for e in ev if e[0] == "load"]
             assert len(loads) == 8 * nk64                     # one tile (8 instructions of this wave) per K step
@@ -127,8 +128,9 @@ def test_both_wave_groups_execute_the_same_number_of_barriers(layout):
     for w in range(4):
         for nk64 in (1, 2, 3, 8):
             n0 = sum(e[0] == "barrier" for e in run(g.group0(w, layout), initial(0, w, nk64)[0])[0])
-            n1 = sum(e[0] == "barrier" for e in run(g.group1(w, layout), initial(1, w, nk64)[0])[0])
-            assert n0 == n1 == 2 * nk64
+            for nbm in (4, 6, 8):
+                n1 = sum(e[0] == "barrier" for e in run(g.group1(w, layout, nbm), initial(1, w, nk64)[0])[0])
+                assert n0 == n1 == 2 * nk64
 
 
 def test_read_stage_ring_visits_the_tiles_in_order():
