@@ -101,7 +101,6 @@ int32_t launch_problems(std::vector<Problem>& all, int32_t layout, int32_t in_dt
     }
   }
   if (!rects.empty()) {
-    if (rects.size() > 65535) return GSPMD_ERR_UNSUPPORTED;
     const ZeroRect* drects = reinterpret_cast<const ZeroRect*>(static_cast<const char*>(workspace) + prob_bytes);
     const int vec_elems = out_dtype == GSPMD_F32 ? 4 : 8;
     bool vec = true;
@@ -113,13 +112,17 @@ int32_t launch_problems(std::vector<Problem>& all, int32_t layout, int32_t in_dt
     }
     const int64_t per_thread = vec ? vec_elems : 1;
     const unsigned gx = static_cast<unsigned>(std::min<int64_t>(std::max<int64_t>((most / per_thread + 255) / 256, 1), 2048));
-    const dim3 grid(gx, static_cast<unsigned>(rects.size())), block(256);
-    if (out_dtype == GSPMD_F32) {
-      if (vec) hipLaunchKernelGGL((zero_rects_kernel<float, 4>), grid, block, 0, stream, drects);
-      else hipLaunchKernelGGL((zero_rects_kernel<float, 1>), grid, block, 0, stream, drects);
-    } else {
-      if (vec) hipLaunchKernelGGL((zero_rects_kernel<bf16_bits, 8>), grid, block, 0, stream, drects);
-      else hipLaunchKernelGGL((zero_rects_kernel<bf16_bits, 1>), grid, block, 0, stream, drects);
+    for (size_t first = 0; first < rects.size(); first += 65535) {       // grid.y is limited to 65535
+      const unsigned gy = static_cast<unsigned>(std::min<size_t>(rects.size() - first, 65535));
+      const dim3 grid(gx, gy), block(256);
+      const ZeroRect* part = drects + first;
+      if (out_dtype == GSPMD_F32) {
+        if (vec) hipLaunchKernelGGL((zero_rects_kernel<float, 4>), grid, block, 0, stream, part);
+        else hipLaunchKernelGGL((zero_rects_kernel<float, 1>), grid, block, 0, stream, part);
+      } else {
+        if (vec) hipLaunchKernelGGL((zero_rects_kernel<bf16_bits, 8>), grid, block, 0, stream, part);
+        else hipLaunchKernelGGL((zero_rects_kernel<bf16_bits, 1>), grid, block, 0, stream, part);
+      }
     }
     if (hipGetLastError() != hipSuccess) return GSPMD_ERR_DEVICE;
   }

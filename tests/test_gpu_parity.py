@@ -209,6 +209,19 @@ def test_moe_weight_gradient_fill_limits_the_contraction(mode):
     assert not st.out_shard(0)[0].any()      # expert 2 (fill 0) lives in partition 0's first slot: all zeros
 
 
+def test_many_batch_entries_with_empty_and_partly_filled_slots():
+    # 70000 tiny per-entry problems in one launch: two thirds of them have fill 0 (nothing to multiply, the output
+    # block is only zero-filled: more fill rectangles than one launch's grid can index), the rest are partly filled
+    E, C, M, H = 70000, 3, 8, 4
+    w = wl.moe(E=E, C=C, M=M, H=H)
+    fill = (np.arange(E) % 3 == 0).astype(np.int64) * (1 + (np.arange(E) % 2))       # 1, 0, 0, 2, 0, 0, ...
+    lhs, rhs = wl.draw_small_int_bf16(1, w.lhs_shape), wl.draw_small_int_bf16(2, w.rhs_shape)
+    st = Staged(w, lhs, rhs, row_align=0, out_dtype="f32")
+    st.run_grouped(fill=fill)
+    ref = oracle_global(w, lhs, rhs, fill=fill)
+    compare_all_shards(st, w, ref, exact=True)
+
+
 def test_moe_experts_sharded_over_mesh():
     # E split over 2 partitions (batch-partitioned mesh dim), uneven: 3 experts -> shards of 2, last valid 1
     w = wl.moe(E=3, C=200, M=128, H=264)
