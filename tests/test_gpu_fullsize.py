@@ -184,3 +184,19 @@ def test_very_long_contraction_is_exact():
     ref = od.dot_general(wl.bf16_bits_to_f64(lhs), wl.bf16_bits_to_f64(rhs), (), (), (1,), (0,))
     got = st.out_shard(0)
     assert np.array_equal(got, ref)
+
+
+def test_experts_weight_gradient_full_size():
+    # ECM,ECH->EMH: the fill count limits the contraction; 2.1 GB of output, tiles of 8-14 K steps
+    w = wl.moe_wgrad()
+    fill = w.draw_fill()
+    lhs, rhs = w.draw_lhs(), w.draw_rhs()
+    st = Staged(w, lhs, rhs, row_align=8)
+    st.run_grouped(fill=fill)
+    torch.cuda.synchronize()
+    out = out_tensor(st, 0).view(4, 8192, 32768)
+    for e in range(4):
+        f = int(fill[e])
+        m_idx = sample_rows(8192, [256, 4096], seed=130 + e, extra=3)
+        ref = od.dot_general(wl.bf16_bits_to_f64(lhs[e, :f][:, m_idx]), wl.bf16_bits_to_f64(rhs[e, :f]), (), (), (0,), (0,))
+        check(to_f64(out[e, torch.from_numpy(m_idx).cuda()].contiguous()), ref, f"ECM,ECH->EMH expert {e}")
