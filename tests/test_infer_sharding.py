@@ -101,3 +101,6 @@ def test_oracle_definition_rejects_wrong_merges():
     assert not ob.is_merged_sharding((4, 8), tuple(range(32)), (64, 48), (0, -1), [(0, (64, 32), (0, -1), 0), (1, (32, 48), (-1, 1), 1)])
     # an output split on a dimension no operand splits is not a merge either
     assert not ob.is_merged_sharding((4, 8), tuple(range(32)), (64, 48), (0, 1), [(0, (64, 32), (0, -1), 0), (1, (32, 48), (-1, -1), 1)])
+    # Offset equality, not an inequality: an output whose shards start later than the operand's on every device
+    assert not ob.is_merged_sharding((4,), (0, 1, 2, 3), (64,), (0,), [(0, (32,), (0,), 0)])
+    assert not ob.is_merged_sharding((4,), (0, 1, 2, 3), (32,), (0,), [(0, (64,), (0,), 0)])
