@@ -159,3 +159,104 @@ def test_config_lowerings():
     d = g.plan_dot(g.Mesh(w.mesh_shape, w.device_ids), g.DotDims((), (), (1,), (0,)), g.Sharding(w.lhs_shape, w.lhs_map),
                    g.Sharding(w.rhs_shape, w.rhs_map), g.Sharding(w.out_shape, w.out_map), 13, 0, 1256, 1256)
     assert len(d) == 1 and (d[0]["m_valid"], d[0]["n_valid"], d[0]["k_valid"], d[0]["ldb"], d[0]["ldc"]) == (1500, 1250, 12288, 1256, 1256)
+
+
+def _check_all_partitions(lhs, rhs, dims, mshape, ids, lmap, rmap, omap, fill=None, fill_dim=None):
+    """Run every partition's plan with numpy on poisoned shards and compare with the oracle's out shard."""
+    mesh, gd = g.Mesh(mshape, ids), g.DotDims(*dims)
+    ref_lhs = lhs if fill is None else od.apply_fill(lhs, dims[0], fill_dim, fill)
+    out_global = od.dot_general(ref_lhs, rhs, *dims)
+    lsh, rsh, osh = g.Sharding(lhs.shape, lmap), g.Sharding(rhs.shape, rmap), g.Sharding(out_global.shape, omap)
+    contracting = g.AXIS_CONTRACTING in g.classify_dot(mesh, gd, lsh, rsh, osh)
+    for pid in range(len(ids)):
+        descs = g.plan_dot(mesh, gd, lsh, rsh, osh, pid, lhs_fill=fill)
+        a, _, _, _ = make_shard(lhs, mshape, ids, lmap, pid, 0)
+        b, _, _, _ = make_shard(rhs, mshape, ids, rmap, pid, 0)
+        cbuf, cview, _, _ = make_shard(np.full(out_global.shape, 7.0), mshape, ids, omap, pid, 0, poison=7.0)
+        run_plan(descs, a, b, cbuf)
+        want_full = od.expected_partial(ref_lhs, rhs, dims, mshape, ids, lmap, rmap, pid) if contracting else out_global
+        want = od.expected_out_shard(want_full, mshape, ids, omap, pid)
+        assert np.array_equal(cview, want), (pid, descs)
+
+
+def test_contracting_dims_listed_in_any_order():
+    # the pairs (lhs 2, rhs 1) and (lhs 1, rhs 0) listed innermost first: a sum does not depend on the order
+    rng = np.random.default_rng(5)
+    lhs = rng.integers(-4, 5, size=(4, 3, 5)).astype(np.float64)
+    rhs = rng.integers(-4, 5, size=(3, 5, 6)).astype(np.float64)
+    _check_all_partitions(lhs, rhs, ((), (), (2, 1), (1, 0)), (2,), (1, 0), (0, -1, -1), (-1, -1, -1), (0, -1))
+    _check_all_partitions(lhs, rhs, ((), (), (1, 2), (0, 1)), (2,), (1, 0), (0, -1, -1), (-1, -1, -1), (0, -1))
+
+
+@st.composite
+def filled_dot(draw):
+    """Mixture-of-experts shapes (Section 5.4): batch dims lead, the capacity dim follows and is partly occupied.
+    kind 'free': [b.., C, M] x [b.., M, H]; kind 'contract': [b.., C, (T,) M] x [b.., C, (T,) H] summed over C (and T)."""
+    nb = draw(st.integers(1, 2))
+    bs = [draw(st.integers(1, 4)) for _ in range(nb)]
+    C, M, H = draw(st.integers(1, 9)), draw(st.integers(1, 6)), draw(st.integers(1, 6))
+    kind = draw(st.sampled_from(["free", "contract", "contract2"]))
+    T = draw(st.integers(2, 3))
+    bdims = tuple(range(nb))
+    if kind == "free":
+        lshape, rshape, oshape = bs + [C, M], bs + [M, H], bs + [C, H]
+        dims = (bdims, bdims, (nb + 1,), (nb,))
+        splittable = {"b%d" % i: (i, i, i) for i in range(nb)}          # name -> (lhs dim, rhs dim, out dim)
+        splittable.update({"C": (nb, None, nb), "M": (nb + 1, nb, None), "H": (None, nb + 1, nb + 1)})
+    elif kind == "contract":
+        lshape, rshape, oshape = bs + [C, M], bs + [C, H], bs + [M, H]
+        dims = (bdims, bdims, (nb,), (nb,))
+        splittable = {"b%d" % i: (i, i, i) for i in range(nb)}
+        splittable.update({"C": (nb, nb, None), "M": (nb + 1, None, nb), "H": (None, nb + 1, nb + 1)})
+    else:
+        lshape, rshape, oshape = bs + [C, T, M], bs + [C, T, H], bs + [M, H]
+        dims = (bdims, bdims, (nb, nb + 1), (nb, nb + 1))
+        splittable = {"b%d" % i: (i, i, i) for i in range(nb)}
+        splittable.update({"C": (nb, nb, None), "M": (nb + 2, None, nb), "H": (None, nb + 2, nb + 1)})
+    mrank = draw(st.integers(1, 2))
+    mshape = tuple(draw(st.integers(1, 3)) for _ in range(mrank))
+    ids = tuple(draw(st.permutations(list(range(int(np.prod(mshape)))))))
+    lmap, rmap, omap = [-1] * len(lshape), [-1] * len(rshape), [-1] * len(oshape)
+    names = sorted(splittable)
+    for axis in range(mrank):
+        if not names or draw(st.booleans()):
+            continue
+        name = names.pop(draw(st.integers(0, len(names) - 1)))
+        ld, rd, odim = splittable[name]
+        if ld is not None:
+            lmap[ld] = axis
+        if rd is not None:
+            rmap[rd] = axis
+        if odim is not None:
+            omap[odim] = axis
+    fill = np.array([draw(st.integers(0, C)) for _ in range(int(np.prod(bs)))], dtype=np.int64)
+    return dict(lshape=tuple(lshape), rshape=tuple(rshape), dims=dims, mshape=mshape, ids=ids, lmap=tuple(lmap), rmap=tuple(rmap),
+                omap=tuple(omap), fill=fill, fill_dim=nb, seed=draw(st.integers(0, 1 << 30)))
+
+
+@settings(max_examples=300, deadline=None, suppress_health_check=[HealthCheck.too_slow])
+@given(filled_dot())
+def test_fill_counts_clamp_rows_or_the_contracted_extent(c):
+    rng = np.random.default_rng(c["seed"])
+    lhs = rng.integers(-4, 5, size=c["lshape"]).astype(np.float64)
+    rhs = rng.integers(-4, 5, size=c["rshape"]).astype(np.float64)
+    # unoccupied slots hold NaN in the shard buffers: the fill count, not the data, must keep them out
+    poisoned = np.array(lhs, copy=True)
+    bshape = c["lshape"][:c["fill_dim"]]
+    for gidx, idx in enumerate(np.ndindex(*bshape)):
+        poisoned[idx + (slice(int(c["fill"][gidx]), None),)] = np.nan
+    mesh, gd = g.Mesh(c["mshape"], c["ids"]), g.DotDims(*c["dims"])
+    ref_lhs = od.apply_fill(lhs, c["dims"][0], c["fill_dim"], c["fill"])
+    out_global = od.dot_general(ref_lhs, rhs, *c["dims"])
+    lsh, rsh, osh = g.Sharding(c["lshape"], c["lmap"]), g.Sharding(c["rshape"], c["rmap"]), g.Sharding(out_global.shape, c["omap"])
+    contracting = g.AXIS_CONTRACTING in g.classify_dot(mesh, gd, lsh, rsh, osh)
+    for pid in range(len(c["ids"])):
+        descs = g.plan_dot(mesh, gd, lsh, rsh, osh, pid, lhs_fill=c["fill"])
+        a, _, _, _ = make_shard(poisoned, c["mshape"], c["ids"], c["lmap"], pid, 0)
+        b, _, _, _ = make_shard(rhs, c["mshape"], c["ids"], c["rmap"], pid, 0)
+        cbuf, cview, _, _ = make_shard(np.full(out_global.shape, 7.0), c["mshape"], c["ids"], c["omap"], pid, 0, poison=7.0)
+        run_plan(descs, a, b, cbuf)
+        want_full = (od.expected_partial(ref_lhs, rhs, c["dims"], c["mshape"], c["ids"], c["lmap"], c["rmap"], pid)
+                     if contracting else out_global)
+        want = od.expected_out_shard(want_full, c["mshape"], c["ids"], c["omap"], pid)
+        assert np.array_equal(cview, want), (pid, descs)
