@@ -431,6 +431,47 @@ def test_relu_epilogue(mode):
     compare_all_shards(st, w, od.relu(oracle_global(w, lhs, rhs)), fro_tol=1e-5)
 
 
+def _check_with_non_finite(got, ref, what):
+    """NaN where the reference is NaN, the same infinity where it is infinite, the usual tolerance elsewhere."""
+    assert got.shape == ref.shape, what
+    assert np.array_equal(np.isnan(got), np.isnan(ref)), what
+    inf = np.isinf(ref)
+    assert np.array_equal(np.isinf(got), inf) and np.array_equal(got[inf], ref[inf]), what
+    fin = np.isfinite(ref)
+    check(np.where(fin, got, 0.0), np.where(fin, ref, 0.0), what=what)
+
+
+@pytest.mark.parametrize("out_dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("N,row_align", [(528, 8), (527, 0)])       # MFMA path; fallback kernel (rows not 16-byte aligned)
+@pytest.mark.parametrize("split_k", [False, True])
+def test_non_finite_values_in_the_valid_region_propagate(out_dtype, N, row_align, split_k):
+    # masking (Section 4.1) is about the padding only: an infinity or NaN that is part of the data must reach the
+    # output as IEEE arithmetic says (inf * 0 and inf - inf give NaN), also through the sum of partials and the Relu
+    M, K = 520, 200
+    if split_k:
+        w = wl.ksplit(M=M, K=K, N=N, P=4)
+    else:
+        w = wl.mesh2d(M=M, K=K, N=N, X=2, Y=1, cfg=7)
+    lhs, rhs = wl.draw_normal_bf16(11, (M, K)), wl.draw_normal_bf16(12, (K, N), 0.05)
+    lhs, rhs = lhs.copy(), rhs.copy()
+    POS_INF, NEG_INF, NAN = 0x7F80, 0xFF80, 0x7FC0
+    lhs[3, 5] = POS_INF          # row 3 becomes +-inf by the sign of rhs[5, :] ...
+    rhs[5, 40] = 0               # ... and NaN where that is zero
+    lhs[300, 7] = NEG_INF
+    lhs[300, 150] = POS_INF      # columns where rhs[7, n] and rhs[150, n] have the same sign: inf - inf = NaN
+    lhs[10, 0] = NAN             # a NaN row
+    rhs[100, 17] = POS_INF       # a column of infinities (NaN where it meets the rows above)
+    with np.errstate(invalid="ignore", over="ignore"):
+        ref = oracle_global(w, lhs, rhs)
+        assert np.isnan(ref[3, 40]) and np.isinf(ref[3, 41]) and np.isnan(ref[10]).all() and np.isnan(ref[300]).any()
+        for epilogue, want_global in ((g.EPILOGUE_NONE, ref), (g.EPILOGUE_RELU, od.relu(ref))):
+            st = Staged(w, lhs, rhs, row_align=row_align, out_dtype=out_dtype)
+            st.run_grouped(epilogue=epilogue)
+            for pid in range(st.P):
+                want = od.expected_out_shard(want_global, w.mesh_shape, w.device_ids, w.out_map, pid)
+                _check_with_non_finite(st.out_shard(pid), want, f"pid {pid} epilogue {epilogue}")
+
+
 def test_relu_is_applied_after_the_sum_of_partials():
     w = wl.ksplit(M=300, K=1000, N=264, P=4)
     lhs, rhs = wl.draw_small_int_bf16(1, w.lhs_shape), wl.draw_small_int_bf16(2, w.rhs_shape)
