@@ -200,3 +200,52 @@ def test_experts_weight_gradient_full_size():
         m_idx = sample_rows(8192, [256, 4096], seed=130 + e, extra=3)
         ref = od.dot_general(wl.bf16_bits_to_f64(lhs[e, :f][:, m_idx]), wl.bf16_bits_to_f64(rhs[e, :f]), (), (), (0,), (0,))
         check(to_f64(out[e, torch.from_numpy(m_idx).cuda()].contiguous()), ref, f"ECM,ECH->EMH expert {e}")
+
+
+def test_reduce_partials_full_size():
+    # the public sum of config 3's four fp32 partials [4096, 8192] -> fp32 and -> bf16, in the benchmark's launch shape
+    import paper_2105_04663_amd as g
+    n = 4096 * 8192
+    rng = np.random.default_rng(33)
+    parts = [rng.standard_normal(n, dtype=np.float32) * np.float32(10.0 ** (p - 1)) for p in range(4)]
+    dev = [torch.from_numpy(p).cuda() for p in parts]
+    ref = np.zeros(n, dtype=np.float64)
+    for p in parts:
+        ref += p.astype(np.float64)
+    stream = torch.cuda.current_stream().cuda_stream
+    out32 = torch.full((n,), float("nan"), device="cuda")
+    g.reduce_partials([t.data_ptr() for t in dev], n, out32.data_ptr(), g.F32, stream)
+    out16 = torch.full((n,), float("nan"), dtype=torch.bfloat16, device="cuda")
+    g.reduce_partials([t.data_ptr() for t in dev], n, out16.data_ptr(), g.BF16, stream)
+    torch.cuda.synchronize()
+    got32 = out32.cpu().numpy().astype(np.float64)
+    # three fp32 additions in a fixed order: each rounds to half an ulp of a partial sum that is at most sum |p_i|
+    bound = 3 * 2.0 ** -24 * sum(np.abs(p.astype(np.float64)) for p in parts)
+    assert (np.abs(got32 - ref) <= bound).all()
+    # and exactly the ascending order: ((p0 + p1) + p2) + p3 in fp32
+    assert np.array_equal(out32.cpu().numpy(), ((parts[0] + parts[1]) + parts[2]) + parts[3])
+    check(to_f64(out16), ref, "reduce to bf16")
+
+
+def test_reshard_allgather_full_size():
+    # the AllGather of BSM [8, 2048, 8192] along M that the benchmark times: four shards [8, 2048, 2048] -> whole, bit for bit
+    import paper_2105_04663_amd as g
+    shape, P = (8, 2048, 8192), 4
+    mesh = g.Mesh((P,), tuple(range(P)))
+    src_sh, dst_sh = g.Sharding(shape, (-1, -1, 0)), g.Sharding(shape, (-1, -1, -1))
+    rng = np.random.default_rng(34)
+    glob = rng.integers(0, 1 << 16, size=shape, dtype=np.uint16)
+    glob[(glob & 0x7F80) == 0x7F80] = 0x3F80          # keep every bit pattern a number, the comparison is on bits anyway
+    srcs = []
+    for p in range(P):
+        off, valid, shard = ob.shard_bounds((P,), tuple(range(P)), shape, (-1, -1, 0), p)
+        piece = np.ascontiguousarray(glob[:, :, off[2]:off[2] + valid[2]])
+        srcs.append(torch.from_numpy(piece.view(np.int16)).cuda().view(torch.bfloat16))
+    dst = torch.zeros(shape, dtype=torch.bfloat16, device="cuda")
+    n = g.reshard_workspace_bytes(mesh)
+    ws = torch.empty(n + 256, dtype=torch.uint8, device="cuda")
+    base = (ws.data_ptr() + 255) // 256 * 256
+    g.reshard(mesh, src_sh, [g.ShardBuf.of(t, 0) for t in srcs], dst_sh, [g.ShardBuf.of(dst, 0)] * P, base, n,
+              torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert np.array_equal(dst.view(torch.int16).cpu().numpy().view(np.uint16), glob)
