@@ -512,6 +512,30 @@ def test_attention_projection_einsums_small(scatter):
     check(st.assemble(), ref, what="BSM reassembled")
 
 
+@pytest.mark.parametrize("align", [8, 0])
+def test_attention_score_einsums_small(align):
+    # Section 5.1's attention between the projections: heads are a batch dimension that sits in the middle of the
+    # operands (BSND layout); B = 3 over X = 2, N = 5 heads over Y = 2, both uneven
+    # BSND,BTND->BNST: both operands have the contracting dimension D last
+    w = _generic((3, 50, 5, 24), (3, 60, 5, 24), (0, 2), (0, 2), (3,), (3,), (2, 2), (0, -1, 1, -1), (0, -1, 1, -1), (0, 1, -1, -1))
+    lhs, rhs = wl.draw_normal_bf16(1, w.lhs_shape), wl.draw_normal_bf16(2, w.rhs_shape, 0.2)
+    st = Staged(w, lhs, rhs, row_align=align)
+    assert g.classify_dot(st.mesh, st.dims, st.lhs_sh, st.rhs_sh, st.out_sh) == (g.AXIS_BATCH, g.AXIS_BATCH)
+    st.run_grouped()
+    ref = oracle_global(w, lhs, rhs)
+    compare_all_shards(st, w, ref)
+    check(st.assemble(), ref, what="BNST reassembled")
+    # BNST,BTND->BNSD: T contracts; it is the last dimension of the lhs and an outer dimension of the rhs
+    w = _generic((3, 5, 50, 64), (3, 64, 5, 24), (0, 1), (0, 2), (3,), (1,), (2, 2), (0, 1, -1, -1), (0, -1, 1, -1), (0, 1, -1, -1))
+    lhs, rhs = wl.draw_normal_bf16(3, w.lhs_shape, 0.2), wl.draw_normal_bf16(4, w.rhs_shape)
+    st = Staged(w, lhs, rhs, row_align=align)
+    assert g.classify_dot(st.mesh, st.dims, st.lhs_sh, st.rhs_sh, st.out_sh) == (g.AXIS_BATCH, g.AXIS_BATCH)
+    st.run_grouped()
+    ref = oracle_global(w, lhs, rhs)
+    compare_all_shards(st, w, ref)
+    check(st.assemble(), ref, what="BNSD reassembled")
+
+
 def test_second_layer_einsums_small():
     # BSH,HM->BSM with H split over 4 partitions (uneven: 1000/4 = 250, rows padded to 256) and bf16 output of the sum
     w = wl.ffn_second(B=3, S=70, H=1000, M=264, Y=4)
