@@ -472,6 +472,21 @@ def test_non_finite_values_in_the_valid_region_propagate(out_dtype, N, row_align
                 _check_with_non_finite(st.out_shard(pid), want, f"pid {pid} epilogue {epilogue}")
 
 
+@pytest.mark.parametrize("N,row_align", [(528, 8), (527, 0)])       # MFMA path; fallback kernel
+def test_denormals_are_kept(N, row_align):
+    # the oracle is exact arithmetic on the input values, so nothing may be flushed to zero: bf16 denormal inputs
+    # (2^-127) times 2^20 give normal sums, 2^-70 x 2^-70 gives fp32 denormal sums; powers of two keep every sum exact
+    M, K = 260, 96
+    w = wl.mesh2d(M=M, K=K, N=N, X=1, Y=1, cfg=7)
+    for a_bits, b_bits in ((0x0040, 0x4980), (0x1C80, 0x1C80)):
+        lhs, rhs = np.full((M, K), a_bits, dtype=np.uint16), np.full((K, N), b_bits, dtype=np.uint16)
+        ref = oracle_global(w, lhs, rhs)
+        assert ref[0, 0] != 0 and float(np.float32(ref[0, 0])) == ref[0, 0]
+        st = Staged(w, lhs, rhs, row_align=row_align, out_dtype="f32")
+        st.run_local(0)
+        compare_all_shards(st, w, ref, exact=True)
+
+
 def test_relu_is_applied_after_the_sum_of_partials():
     w = wl.ksplit(M=300, K=1000, N=264, P=4)
     lhs, rhs = wl.draw_small_int_bf16(1, w.lhs_shape), wl.draw_small_int_bf16(2, w.rhs_shape)
