@@ -487,6 +487,34 @@ def test_denormals_are_kept(N, row_align):
         compare_all_shards(st, w, ref, exact=True)
 
 
+@pytest.mark.parametrize("kind", ["mfma", "fallback", "sum_of_partials"])
+def test_bf16_output_rounds_to_nearest_even(kind):
+    # out[m, n] = v_n + j_m * 2^-9 with v_n a bf16 value in [1, 2) (ulp 2^-7) and j_m in 0..7: exact in fp32, and
+    # j = 2 and 6 are ties that must go to the even neighbour.  Expected bits: torch's fp32 -> bf16 conversion on the CPU.
+    M, K, N = 552, 16, (527 if kind == "fallback" else 536)
+    rng = np.random.default_rng(21)
+    lhs64, rhs64 = np.zeros((M, K)), np.zeros((K, N))
+    lhs64[:, 0], lhs64[:, K - 1] = 1.0, rng.integers(0, 8, size=M)
+    rhs64[0, :], rhs64[K - 1, :] = 1.0 + rng.integers(0, 128, size=N) / 128.0, 2.0 ** -9
+    lhs, rhs = wl.f32_to_bf16_bits(lhs64.astype(np.float32)), wl.f32_to_bf16_bits(rhs64.astype(np.float32))
+    assert np.array_equal(wl.bf16_bits_to_f64(lhs), lhs64) and np.array_equal(wl.bf16_bits_to_f64(rhs), rhs64)
+    if kind == "sum_of_partials":
+        w = wl.ksplit(M=M, K=K, N=N, P=2)        # the two terms of every sum come from different partitions
+    else:
+        w = wl.mesh2d(M=M, K=K, N=N, X=1, Y=1, cfg=7)
+    ref = oracle_global(w, lhs, rhs)
+    want = torch.from_numpy(ref.astype(np.float32)).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(ref.astype(np.float32).astype(np.float64), ref)
+    st = Staged(w, lhs, rhs, row_align=(0 if kind == "fallback" else 8), out_dtype="bf16")
+    st.run_grouped()
+    torch.cuda.synchronize()
+    _, t, ld, shard = st.out[0]
+    got = t[:M * ld].view(M, ld)[:, :N].contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+    assert np.array_equal(got, want)
+    ties = (lhs64[:, K - 1] % 4 == 2)
+    assert ties.sum() > 50
+
+
 def test_relu_is_applied_after_the_sum_of_partials():
     w = wl.ksplit(M=300, K=1000, N=264, P=4)
     lhs, rhs = wl.draw_small_int_bf16(1, w.lhs_shape), wl.draw_small_int_bf16(2, w.rhs_shape)
