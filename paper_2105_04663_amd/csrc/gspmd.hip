@@ -19,6 +19,12 @@ constexpr int64_t kWsAlign = 256;
 
 bool is_dtype(int32_t d) { return d == GSPMD_F32 || d == GSPMD_BF16; }
 
+// A tensor with a zero-size dimension has no elements; its buffers may be null pointers.
+bool has_no_elements(const gspmd_sharding* sh) {
+  for (int i = 0; i < sh->rank; ++i) if (sh->global_shape[i] == 0) return true;
+  return false;
+}
+
 int32_t check_buf(const gspmd_shard_buf* b) {
   if (!b) return GSPMD_ERR_NULL;
   if (!is_dtype(b->dtype)) return GSPMD_ERR_UNSUPPORTED;
@@ -548,6 +554,7 @@ static int32_t shard_copy(const gspmd_mesh* mesh, const gspmd_sharding* sh, int6
   if (st != GSPMD_OK) return st;
   if ((st = validate_sharding(mesh, sh)) != GSPMD_OK) return st;
   if ((st = check_buf(shard)) != GSPMD_OK) return st;
+  if (has_no_elements(sh)) return GSPMD_OK;   // nothing to copy
   if (!shard->data || (extract ? !src_global : !dst_global)) return GSPMD_ERR_NULL;
   Bounds b;
   if ((st = shard_bounds(mesh, sh, pid, &b)) != GSPMD_OK) return st;
@@ -632,8 +639,9 @@ int32_t gspmd_reshard(const gspmd_mesh* mesh, const gspmd_sharding* src_sh, cons
     if (src_shards[p].dtype != dtype || dst_shards[p].dtype != dtype) return GSPMD_ERR_UNSUPPORTED;
     if (src_shards[p].row_stride != src_shards[0].row_stride || dst_shards[p].row_stride != dst_shards[0].row_stride)
       return GSPMD_ERR_BAD_BUFFER;
-    if (!src_shards[p].data || !dst_shards[p].data) return GSPMD_ERR_NULL;
+    if (!has_no_elements(src_sh) && (!src_shards[p].data || !dst_shards[p].data)) return GSPMD_ERR_NULL;
   }
+  if (has_no_elements(src_sh)) return GSPMD_OK;   // same global shape on both sides: nothing to move
   int64_t need = 0;
   if ((st = gspmd_reshard_workspace_bytes(mesh, &need)) != GSPMD_OK) return st;
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kWsAlign - 1)) || workspace_bytes < need) return GSPMD_ERR_WORKSPACE;

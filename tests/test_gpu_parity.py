@@ -515,6 +515,23 @@ def test_bf16_output_rounds_to_nearest_even(kind):
     assert ties.sum() > 50
 
 
+@pytest.mark.parametrize("mesh_shape,lmap,rmap,omap", [((1,), (-1, -1), (-1, -1), (-1, -1)), ((2,), (0, -1), (-1, -1), (0, -1)),
+                                                    ((2,), (-1, 0), (0, -1), (-1, -1))])
+def test_empty_dimensions(mesh_shape, lmap, rmap, omap):
+    # an empty contracting dimension sums nothing: the output is all zeros (and is written); an empty non-contracting
+    # dimension leaves nothing to write and the call is a no-op that succeeds
+    for lshape, rshape in (((40, 0), (0, 24)), ((0, 16), (16, 24)), ((40, 16), (16, 0))):
+        w = _generic(lshape, rshape, (), (), (1,), (0,), mesh_shape, lmap, rmap, omap, out_dtype="f32")
+        lhs, rhs = np.zeros(lshape, dtype=np.uint16), np.zeros(rshape, dtype=np.uint16)
+        st = Staged(w, lhs, rhs, row_align=8)
+        st.run_grouped()
+        for pid in range(st.P):
+            st.run_local(pid, out_override=None)
+        ref = oracle_global(w, lhs, rhs)
+        assert ref.shape == (lshape[0], rshape[1])
+        compare_all_shards(st, w, ref, exact=True)
+
+
 def test_relu_is_applied_after_the_sum_of_partials():
     w = wl.ksplit(M=300, K=1000, N=264, P=4)
     lhs, rhs = wl.draw_small_int_bf16(1, w.lhs_shape), wl.draw_small_int_bf16(2, w.rhs_shape)
