@@ -31,16 +31,9 @@
 #include "kernels_basic.h"
 #include "mainloop_asm.h"
 #include "plan.h"
+#include "tile_index.h"
 
 namespace gspmd {
-
-constexpr int kMfmaBM = 256, kMfmaBN = 256, kMfmaBK = 32;
-constexpr int kMfmaThreads = 512;
-constexpr int kStageA = kMfmaBM * kMfmaBK * 2;     // 16 KiB
-constexpr int kStageB = kMfmaBK * kMfmaBN * 2;     // 16 KiB
-constexpr int kStage = kStageA + kStageB;
-constexpr int kNumStages = 5;
-constexpr int kMfmaLds = kNumStages * kStage;      // all 160 KiB of the CU's LDS
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(4))) short short4_t;
@@ -49,9 +42,6 @@ typedef __attribute__((ext_vector_type(16))) float float16_t;
 typedef __attribute__((ext_vector_type(4))) float float4_t;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 typedef __attribute__((address_space(3))) short4_t lds_short4_t;
-
-__device__ __forceinline__ int swz_a(int row) { return (row >> 1) & 3; }
-__device__ __forceinline__ int swz_b(int krow) { return ((krow & 3) << 2) ^ (((krow >> 3) & 1) << 1); }
 
 // s_waitcnt immediate for gfx9: vmcnt [3:0]+[15:14], expcnt [6:4], lgkmcnt [11:8]
 constexpr int waitcnt_imm(int vm, int lgkm) { return (vm & 15) | ((vm >> 4) << 14) | (7 << 4) | ((lgkm & 15) << 8); }
@@ -73,73 +63,6 @@ __device__ __forceinline__ u32x4_t mask_tail8(u32x4_t v, int keep) {   // keep f
   return v;
 }
 
-// Which output tile a workgroup takes.  Workgroup b runs on XCD b % 8 (each XCD has its own L2), and 256
-// workgroups are resident at a time.  Within every window of 256 consecutive tile ids XCD x takes ids
-// [32x, 32x+32), and inside a problem ids walk bands of 8 tile rows with the row index running fastest: an
-// XCD's 32 concurrent tiles then form a block of about 8 rows x 4 columns (12 operand panels per K step instead
-// of up to 33), and a problem with few tile rows (an expert with <= 1024 occupied slots) streams every weight
-// panel exactly once, all its row tiles being in flight together.
-__device__ __forceinline__ int logical_tile(int b, int total) {
-  const int full = total & ~255;
-  if (b >= full) return b;
-  const int r = b & 255;
-  return (b & ~255) + (r & 7) * 32 + (r >> 3);
-}
-
-constexpr int kBandRows = 8;
-
-__device__ __forceinline__ int swz_h(int row) { return (row >> 1) & 7; }
-
-// Main loop, K-contiguous operand: part `half` (0/1) of a 64-wide K step is [128 rows][64 k] with 128-byte rows.
-// Per-lane byte offset, relative to the address of (first row of the 256-row tile, first k of the step), of load
-// instruction q (0..15; rows 8q..8q+7 of the half, 8 lanes per row).  Rows past the valid extent reuse the last
-// valid row (their results are never stored).
-__device__ __forceinline__ int kc_half_load_offset(int q, int lane, int half, int r0, int rows_valid, int ld) {
-  const int r = q * 8 + (lane >> 3);
-  const int c = (lane & 7) ^ swz_h(r);
-  const int rr = min(r0 + half * 128 + r, rows_valid - 1) - r0;
-  return (rr * ld + c * 8) * 2;
-}
-// LDS byte offset inside the part of a lane's first fragment (first 32 k of the step; the second at ^ 64) of the
-// 16-row block whose first row inside the half is `base`; block b at + b * 2048.
-__device__ __forceinline__ int kc_half_frag_offset(int base, int lane) {
-  const int row = base + (lane & 15);
-  return row * 128 + (((lane >> 4) ^ swz_h(row)) << 4);
-}
-
-// What is left of K after the main loop uses [256 rows][32 k] parts for a K-contiguous operand:
-// per-lane byte offset, relative to the tile's base, of load instruction q (0..15) of a K-contiguous operand tile
-// ([256 rows][32 k]: instruction q covers rows 16q..16q+15, 4 lanes per row).  Rows past the valid extent reuse the
-// last valid row (their results are never stored).
-__device__ __forceinline__ int kc_load_offset(int q, int lane, int r0, int rows_valid, int ld) {
-  const int r = q * 16 + (lane >> 2);
-  const int c = (lane & 3) ^ swz_a(r);
-  const int rr = min(r0 + r, rows_valid - 1) - r0;
-  return (rr * ld + c * 8) * 2;
-}
-// Same for a K-major operand tile ([32 k][256 columns]: instruction q covers k rows 2q, 2q+1, 32 lanes per row).
-// 16-byte chunks past the valid extent reuse the last valid chunk.
-__device__ __forceinline__ int km_load_offset(int q, int lane, int c0, int cols_valid, int ld) {
-  const int kr = q * 2 + (lane >> 5);
-  const int cn = (lane & 31) ^ swz_b(kr);
-  int n = c0 + cn * 8;
-  if (n >= cols_valid) n = ((cols_valid - 1) >> 3) << 3;
-  return (kr * ld + (n - c0)) * 2;
-}
-// LDS byte offset (inside the operand's part of a stage) of a lane's fragment of 16-row block 0 whose first row is
-// `base`: K-contiguous tile, block b at + b * 1024.
-__device__ __forceinline__ int kc_frag_offset(int base, int lane) {
-  const int row = base + (lane & 15);
-  return row * 64 + (((lane >> 4) ^ swz_a(row)) << 4);
-}
-// K-major tile (read with the transpose read): block b at ^ (b << 5), second half of the fragment at + 4 * 512.
-__device__ __forceinline__ int km_frag_offset(int base, int lane) {
-  const int i = lane & 15;
-  const int krow = (lane >> 4) * 8 + (i >> 2);
-  const int cl = base + (i & 3) * 4;
-  return krow * 512 + (((cl >> 3) ^ swz_b(krow)) << 4) + (cl & 7) * 2;
-}
-
 template <typename TOut, int LAYOUT>
 __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const Problem* __restrict__ tab, int n_prob, int epilogue) {
   constexpr bool AKM = (LAYOUT & GSPMD_LAYOUT_LHS_K_MAJOR) != 0, BKC = (LAYOUT & GSPMD_LAYOUT_RHS_K_CONTIGUOUS) != 0;
@@ -150,12 +73,8 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const Problem* _
 
   const int tile = logical_tile(blockIdx.x, gridDim.x);
   const Problem P = tab[find_problem(tab, n_prob, tile)];
-  const int local = tile - P.tile_begin;
-  const int tiles_m = (P.Mv + kMfmaBM - 1) / kMfmaBM;   // tiles cover the valid extents; the rest of the static block is zero-filled apart
-  const int band = local / (kBandRows * P.tiles_n);
-  const int rows_in_band = min(kBandRows, tiles_m - band * kBandRows);
-  const int in_band = local - band * kBandRows * P.tiles_n;
-  const int m0 = (band * kBandRows + in_band % rows_in_band) * kMfmaBM, n0 = (in_band / rows_in_band) * kMfmaBN;
+  int m0, n0;
+  tile_origin(tile - P.tile_begin, P.Mv, P.tiles_n, &m0, &n0);
 
   // acc[bm] holds the four 16x16 tiles (bn = 0..3) of 16-row block bm: element 4*bn + r
   float16_t acc[8];
