@@ -323,6 +323,24 @@ def main():
         others["ksplit_matmul"]["reduce_alone"] = {"kernel": "reduce_partials_kernel", "ms": round(ms, 4), "algorithmic_bytes": rbytes,
                                                    "gbs": round(rbytes / ms / 1e6, 1), "frac_of_hbm_peak": round(rbytes / ms / 1e6 / PEAK_HBM_GBS, 3)}
         del parts, red
+        # the contraction part of config 3 alone: the four partitions' partial products as one launch of four problems
+        # (the partition index as a batch dimension), fp32 partials written, no sum
+        mesh1 = g.Mesh((1,), (0,))
+        pd = g.DotDims((0,), (0,), (2,), (1,))
+        pa = torch.randn(4, 4096, 4096, device=dev).to(torch.bfloat16)
+        pb = (torch.randn(4, 4096, 8192, device=dev) * 0.02).to(torch.bfloat16)
+        pc = torch.empty(4, 4096, 8192, device=dev)
+        psh = [g.Sharding(tuple(t.shape), (-1, -1, -1)) for t in (pa, pb, pc)]
+        pn = g.dot_workspace_bytes(mesh1, pd, psh[0], psh[1], psh[2], -1, False)
+        pws = torch.empty(pn + 256, dtype=torch.uint8, device=dev)
+        pbase = (pws.data_ptr() + 255) // 256 * 256
+        ms = timed_call(lambda: g.grouped_dot(mesh1, pd, [g.ShardBuf.of(pa, 0)], psh[0], [g.ShardBuf.of(pb, 0)], psh[1],
+                                              [g.ShardBuf.of(pc, 0)], psh[2], None, pbase, pn, stream), 20, 3)
+        pfl = 2.0 * 4 * 4096 * 4096 * 8192
+        others["ksplit_matmul"]["gemm_alone"] = {"kernel": "dot_mfma_kernel (fp32 partials)", "ms": round(ms, 4),
+                                                 "tflops": round(pfl / ms / 1e9, 2),
+                                                 "pct_of_peak": round(100.0 * pfl / ms / 1e9 / PEAK_BF16_TFLOPS, 2)}
+        del pa, pb, pc, pws
         mesh4 = g.Mesh((4,), (0, 1, 2, 3))
         shp = (8, 2048, 8192)
         src_sh, dst_sh = g.Sharding(shp, (-1, -1, 0)), g.Sharding(shp, (-1, -1, -1))
