@@ -285,16 +285,28 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const Problem* _
         *reinterpret_cast<u32x4_t*>(c0 + static_cast<int64_t>(p * 8) * P.ldc) = v;
       }
     } else {
-      TOut* __restrict__ c0 = Cg + static_cast<int64_t>(m0 + wm * 128 + (lane & 15)) * P.ldc + n0 + wn * 64 + (lane >> 4) * 4;
+      // fp32: a row of the wave's block is 256 bytes, of which a lane holds 16 per 16-column block.  Staged through the
+      // wave's LDS slice in two passes of 64 rows (rows padded to 272 bytes) and stored 16 lanes per row: whole rows.
+      constexpr int kPitch = 272;
+      unsigned char* slice = smem + wave * (128 * 144);
+      TOut* __restrict__ c0 = Cg + static_cast<int64_t>(m0 + wm * 128 + (lane >> 4)) * P.ldc + n0 + wn * 64 + (lane & 15) * 4;
 #pragma unroll
-      for (int bm = 0; bm < 8; ++bm) {
-        TOut* crow = c0 + static_cast<int64_t>(bm * 16) * P.ldc;
+      for (int pass = 0; pass < 2; ++pass) {
 #pragma unroll
-        for (int bn = 0; bn < 4; ++bn) {
-          float v[4];
+        for (int b4 = 0; b4 < 4; ++b4) {
+          const int bm = pass * 4 + b4;
 #pragma unroll
-          for (int j = 0; j < 4; ++j) v[j] = apply_epilogue(acc[bm][bn * 4 + j], epilogue);
-          *reinterpret_cast<float4*>(crow + bn * 16) = make_float4(v[0], v[1], v[2], v[3]);
+          for (int bn = 0; bn < 4; ++bn) {
+            float4_t v;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] = apply_epilogue(acc[bm][bn * 4 + j], epilogue);
+            *reinterpret_cast<float4_t*>(slice + (b4 * 16 + (lane & 15)) * kPitch + bn * 64 + (lane >> 4) * 16) = v;
+          }
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const float4_t v = *reinterpret_cast<const float4_t*>(slice + (i * 4 + (lane >> 4)) * kPitch + (lane & 15) * 16);
+          *reinterpret_cast<float4_t*>(c0 + static_cast<int64_t>(pass * 64 + i * 4) * P.ldc) = v;
         }
       }
     }
