@@ -170,3 +170,33 @@ def test_resharded_dot_accepts_any_shardings(lshape, rshape, dims, mesh_shape, l
     with pytest.raises(g.GspmdError) as e:
         g.resharded_dot(mesh, gd, [x[0] for x in lb], lsh, [x[0] for x in rb], rsh, [x[0] for x in ob], osh, None, base, n - 256, 0)
     assert e.value.status == 8
+
+
+def test_resharded_dot_with_fill_counts_and_relu():
+    # ECM,EMH->ECH on a 2 x 2 mesh: experts over X in the output, the lhs arrives split on M (contracting, rhs whole) and
+    # on C; the fill counts refer to the global lhs whatever its sharding, and the Relu follows the finished product
+    E, C, M, H = 4, 90, 64, 72
+    mesh_shape, ids = (2, 2), (2, 0, 3, 1)
+    mesh, gd = g.Mesh(mesh_shape, ids), g.DotDims((0,), (0,), (2,), (1,))
+    lhs, rhs = wl.draw_small_int_bf16(5, (E, C, M)), wl.draw_small_int_bf16(6, (E, M, H))
+    fill = np.array([90, 0, 37, 64], dtype=np.int64)
+    a = od.apply_fill(wl.bf16_bits_to_f64(lhs), (0,), 1, fill)
+    ref = od.relu(od.dot_general(a, wl.bf16_bits_to_f64(rhs), (0,), (0,), (2,), (1,)))
+    assert (ref == 0).mean() > 0.3 and (ref > 0).any()
+    lsh, rsh, osh = g.Sharding((E, C, M), (-1, 1, 0)), g.Sharding((E, M, H), (-1, -1, -1)), g.Sharding((E, C, H), (0, -1, 1))
+    with pytest.raises(g.GspmdError) as e:
+        g.classify_dot(mesh, gd, lsh, rsh, osh)
+    assert e.value.status == 6
+    lb = stage(mesh, lsh, to_device(lhs, "bf16"), "bf16", 8, True)
+    rb = stage(mesh, rsh, to_device(rhs, "bf16"), "bf16", 8, True)
+    ob = stage(mesh, osh, None, "f32", 8, True)
+    n = g.resharded_dot_workspace_bytes(mesh, gd, lsh, rsh, osh, g.BF16)
+    ws = torch.empty(n + 256, dtype=torch.uint8, device="cuda")
+    base = (ws.data_ptr() + 255) // 256 * 256
+    g.resharded_dot(mesh, gd, [x[0] for x in lb], lsh, [x[0] for x in rb], rsh, [x[0] for x in ob], osh, fill, base, n,
+                    torch.cuda.current_stream().cuda_stream, g.EPILOGUE_RELU)
+    torch.cuda.synchronize()
+    for pid in range(4):
+        _, t, ld, shard = ob[pid]
+        want = od.expected_out_shard(ref, mesh_shape, ids, (0, -1, 1), pid)
+        assert np.array_equal(read_shard(t, shard, ld), want), pid
