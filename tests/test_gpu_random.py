@@ -12,14 +12,16 @@ from tests.harness import Staged
 pytestmark = pytest.mark.gpu
 
 ORDERS = {"nn": ("blc", "bcr"), "tn": ("bcl", "bcr"), "nt": ("blc", "brc"), "tt": ("bcl", "brc")}
+BIG = [1, 2, 3, 5, 17, 40, 130, 300]           # sizes of the innermost non-contracting dims
+KS = [1, 8, 33, 64, 100, 200, 520]             # sizes of the innermost contracting dim
 
 
 def draw_case(rng):
     nb, nlf, nc, nrf = rng.integers(0, 2), rng.integers(1, 3), rng.integers(1, 3), rng.integers(1, 3)
-    big = lambda: int(rng.choice([1, 2, 3, 5, 17, 40, 130, 300]))
+    big = lambda: int(rng.choice(BIG))
     small = lambda: int(rng.choice([1, 2, 3, 4, 7]))
     sizes = {"b": [small() for _ in range(nb)], "l": [small() for _ in range(nlf - 1)] + [big()],
-             "c": [small() for _ in range(nc - 1)] + [int(rng.choice([1, 8, 33, 64, 100, 200, 520]))],
+             "c": [small() for _ in range(nc - 1)] + [int(rng.choice(KS))],
              "r": [small() for _ in range(nrf - 1)] + [big()]}
     order = str(rng.choice(list(ORDERS)))
     lhs_roles = [(k, i) for k in ORDERS[order][0] for i in range(len(sizes[k]))]
@@ -78,3 +80,11 @@ def test_random_sharded_dots_are_exact(seed):
             assert got.shape == want.shape and np.array_equal(got, want), f"{what} pid {pid}"
         ran += 1
     assert ran >= 20
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_random_sharded_dots_spanning_several_tiles(seed, monkeypatch):
+    # the same sweep with extents around and beyond the MFMA kernel's 256 x 256 tile and 64-wide K step
+    monkeypatch.setattr(__import__(__name__, fromlist=["BIG"]), "BIG", [1, 7, 130, 255, 256, 257, 300, 511, 513, 700, 1100])
+    monkeypatch.setattr(__import__(__name__, fromlist=["KS"]), "KS", [8, 33, 63, 64, 65, 127, 128, 129, 200, 520, 1000, 2050])
+    test_random_sharded_dots_are_exact(500 + seed)
