@@ -200,3 +200,29 @@ def test_resharded_dot_with_fill_counts_and_relu():
         _, t, ld, shard = ob[pid]
         want = od.expected_out_shard(ref, mesh_shape, ids, (0, -1, 1), pid)
         assert np.array_equal(read_shard(t, shard, ld), want), pid
+
+
+def _random_map(rng, rank, mesh_rank):
+    m = [-1] * rank
+    axes = list(rng.permutation(mesh_rank))
+    for d in rng.permutation(rank):
+        if axes and rng.random() < 0.6:
+            m[int(d)] = int(axes.pop())
+    return tuple(m)
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_random_reshards_are_bit_exact(seed):
+    rng = np.random.default_rng(4200 + seed)
+    for case in range(40):
+        rank = int(rng.integers(1, 4))
+        shape = tuple(int(rng.choice([1, 2, 3, 5, 8, 17, 40, 64, 130, 264])) for _ in range(rank))
+        mesh_shape = tuple(int(x) for x in rng.choice([1, 2, 3], size=rng.integers(1, 4)))
+        P = int(np.prod(mesh_shape))
+        ids = tuple(int(x) for x in rng.permutation(P))
+        src_map, dst_map = _random_map(rng, rank, len(mesh_shape)), _random_map(rng, rank, len(mesh_shape))
+        dtype, row_align = (("bf16", 8), ("bf16", 0), ("f32", 0), ("f32", 8))[int(rng.integers(0, 4))]
+        try:
+            run_case(shape, mesh_shape, ids, src_map, dst_map, dtype=dtype, row_align=row_align, share=bool(rng.random() < 0.7))
+        except AssertionError as e:
+            raise AssertionError(f"seed {seed} case {case}: {shape} mesh {mesh_shape} ids {ids} {src_map}->{dst_map} {dtype} align {row_align}: {e}")
