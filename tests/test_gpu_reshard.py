@@ -226,3 +226,45 @@ def test_random_reshards_are_bit_exact(seed):
             run_case(shape, mesh_shape, ids, src_map, dst_map, dtype=dtype, row_align=row_align, share=bool(rng.random() < 0.7))
         except AssertionError as e:
             raise AssertionError(f"seed {seed} case {case}: {shape} mesh {mesh_shape} ids {ids} {src_map}->{dst_map} {dtype} align {row_align}: {e}")
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_random_resharded_dots_are_exact(seed):
+    # any three shardings: the operands are rewritten as the Dot needs them, the result must equal the oracle's slices
+    rng = np.random.default_rng(5200 + seed)
+    for case in range(30):
+        nb = int(rng.integers(0, 2))
+        b = [int(rng.choice([1, 2, 3, 5]))] * nb
+        two_free = bool(rng.random() < 0.4)
+        lf = ([int(rng.choice([2, 3, 4]))] if two_free else []) + [int(rng.choice([1, 5, 40, 130, 300]))]
+        rf = [int(rng.choice([1, 7, 33, 264, 300]))]
+        c = [int(rng.choice([1, 8, 33, 64, 200]))]
+        lshape, rshape = tuple(b + lf + c), tuple(b + c + rf)
+        nl = len(lf)
+        dims = (tuple(range(nb)), tuple(range(nb)), (nb + nl,), (nb,))
+        mesh_shape = tuple(int(x) for x in rng.choice([1, 2, 3], size=rng.integers(1, 4)))
+        P = int(np.prod(mesh_shape))
+        ids = tuple(int(x) for x in rng.permutation(P))
+        oshape = tuple(b + lf + rf)
+        lmap, rmap, omap = (_random_map(rng, len(s), len(mesh_shape)) for s in (lshape, rshape, oshape))
+        row_align = int(rng.choice([0, 8]))
+        what = f"seed {seed} case {case}: {lshape}x{rshape} mesh {mesh_shape} ids {ids} maps {lmap} {rmap} -> {omap} align {row_align}"
+        mesh, gd = g.Mesh(mesh_shape, ids), g.DotDims(*dims)
+        lhs, rhs = wl.draw_small_int_bf16(int(rng.integers(1 << 30)), lshape), wl.draw_small_int_bf16(int(rng.integers(1 << 30)), rshape)
+        ref = od.dot_general(wl.bf16_bits_to_f64(lhs), wl.bf16_bits_to_f64(rhs), *dims)
+        assert ref.shape == oshape
+        lsh, rsh, osh = g.Sharding(lshape, lmap), g.Sharding(rshape, rmap), g.Sharding(oshape, omap)
+        lb = stage(mesh, lsh, to_device(lhs, "bf16"), "bf16", row_align, True)
+        rb = stage(mesh, rsh, to_device(rhs, "bf16"), "bf16", row_align, True)
+        ob = stage(mesh, osh, None, "f32", row_align, True)
+        n = g.resharded_dot_workspace_bytes(mesh, gd, lsh, rsh, osh, g.BF16)
+        ws = torch.empty(n + 256, dtype=torch.uint8, device="cuda")
+        base = (ws.data_ptr() + 255) // 256 * 256
+        g.resharded_dot(mesh, gd, [x[0] for x in lb], lsh, [x[0] for x in rb], rsh, [x[0] for x in ob], osh, None, base, n,
+                        torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        for pid in range(P):
+            _, t, ld, shard = ob[pid]
+            want = od.expected_out_shard(ref, mesh_shape, ids, omap, pid)
+            got = read_shard(t, shard, ld)
+            assert got.shape == want.shape and np.array_equal(got, want), f"{what} pid {pid}"
