@@ -102,7 +102,9 @@ typedef struct {
  * row_stride: distance in elements between consecutive indices of the second-to-last
  * dimension; 0 means dense (= static size of the last dimension).  Outer dimensions are
  * dense on top of it.  A row_stride that is a multiple of 8 elements together with a
- * 16-byte aligned pointer selects the MFMA kernels for bf16.  data may be NULL only for a
+ * 16-byte aligned pointer selects the MFMA kernels for bf16; an operand whose contiguous dimension
+ * is contracted runs fastest when its rows start on 128-byte lines (row_stride a multiple of 64
+ * elements: 9 % faster than a multiple of 8 that is not, at 8200 against 8256).  data may be NULL only for a
  * tensor with a zero-size dimension (no elements: nothing is read or written). */
 typedef struct {
   void* data;          /* device */
