@@ -135,20 +135,28 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const Problem* _
       }
       return v;
     };
-    auto load_tail = [&](int kt, int stage) {
+    // this wave's 4 + 4 chunks of tile kt (the four waves of one group bring a whole tile): global memory -> registers,
+    // then registers -> the [256][32] / [32][256] parts of a stage
+    auto fetch_tail = [&](int kt, u32x4_t (&ta)[4], u32x4_t (&tb)[4]) {
       const int k0 = kt * kMfmaBK;
       const bf16_bits* ab = Abase + kt * a_tile;
       const bf16_bits* bb = Bbase + kt * b_tile;
-      unsigned char* sa = smem + stage * kStage + wn * 4096 + lane * 16;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const int q = wn * 4 + j;
         const int ao = AKM ? km_load_offset(q, lane, m0, P.Mv, P.lda) : kc_load_offset(q, lane, m0, P.Mv, P.lda);
         const int bo = BKC ? kc_load_offset(q, lane, n0, P.Nv, P.ldb) : km_load_offset(q, lane, n0, P.Nv, P.ldb);
-        *reinterpret_cast<u32x4_t*>(sa + j * 1024) = tail_chunk(AKM, ab, ao, q, k0);
-        *reinterpret_cast<u32x4_t*>(sa + kStageA + j * 1024) = tail_chunk(!BKC, bb, bo, q, k0);
+        ta[j] = tail_chunk(AKM, ab, ao, q, k0);
+        tb[j] = tail_chunk(!BKC, bb, bo, q, k0);
       }
-      GSPMD_WAIT_ALL();
+    };
+    auto store_tail = [&](int stage, const u32x4_t (&ta)[4], const u32x4_t (&tb)[4]) {
+      unsigned char* sa = smem + stage * kStage + wn * 4096 + lane * 16;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        *reinterpret_cast<u32x4_t*>(sa + j * 1024) = ta[j];
+        *reinterpret_cast<u32x4_t*>(sa + kStageA + j * 1024) = tb[j];
+      }
     };
     // ---- fragment read offsets inside a stage, for the tail's [256][32] / [32][256] parts
     const int a_frag = AKM ? km_frag_offset(wm * 128, lane) : kc_frag_offset(wm * 128, lane);
@@ -243,16 +251,29 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const Problem* _
         else if constexpr (LAYOUT == 2) { GSPMD_RUN_MAINLOOP(2) }
         else { GSPMD_RUN_MAINLOOP(3) }
       }
-      GSPMD_WAIT_ALL();
-      __syncthreads();
     }
-    // ---- what is left of K (< 64): up to two tiles, the last one possibly partial; not pipelined
-    for (int kt = 2 * nk64; kt * kMfmaBK < P.Kv; ++kt) {
-      if (wm == 0) load_tail(kt, 0);
-      __syncthreads();
-      read_frags(0);
-      mma_all();
-      __syncthreads();
+    // ---- what is left of K (< 64): up to two tiles, the last one possibly partial.  Group 0 fetches the first and
+    // group 1 the second as soon as they leave the loop (group 0 a phase earlier), both in flight together; they go
+    // through registers (zeroed beyond the valid K) into stages 0 and 1 once every load of the loop has landed.
+    const int ntail = (P.Kv - nkt * kMfmaBK + kMfmaBK - 1) / kMfmaBK;
+    {
+      u32x4_t ta[4], tb[4];
+      if (wm < ntail) fetch_tail(nkt + wm, ta, tb);
+      if (nk64 > 0) {
+        GSPMD_WAIT_ALL();
+        __syncthreads();
+      }
+      if (ntail > 0) {
+        if (wm < ntail) store_tail(wm, ta, tb);
+        __syncthreads();
+        read_frags(0);
+        mma_all();
+        if (ntail > 1) {
+          read_frags(1);
+          mma_all();
+        }
+        __syncthreads();
+      }
     }
   }
 
