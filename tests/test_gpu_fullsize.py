@@ -249,3 +249,54 @@ def test_reshard_allgather_full_size():
               torch.cuda.current_stream().cuda_stream)
     torch.cuda.synchronize()
     assert np.array_equal(dst.view(torch.int16).cpu().numpy().view(np.uint16), glob)
+
+
+def test_output_with_more_than_2_31_elements():
+    # [70000, 64] x [64, 32768] -> [70000, 32768] fp32: 2.29e9 output elements (9.2 GB), so every output offset past row
+    # 65535 needs 64-bit arithmetic; small integers make each element exact
+    import paper_2105_04663_amd as g
+    M, K, N = 70000, 64, 32768
+    w = wl.mesh2d(M=M, K=K, N=N, X=1, Y=1, cfg=7)
+    lhs, rhs = wl.draw_small_int_bf16(41, (M, K)), wl.draw_small_int_bf16(42, (K, N))
+    a = torch.from_numpy(lhs.view(np.int16)).cuda().view(torch.bfloat16)
+    b = torch.from_numpy(rhs.view(np.int16)).cuda().view(torch.bfloat16)
+    c = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    mesh, dims = g.Mesh((1,), (0,)), g.DotDims((), (), (1,), (0,))
+    lsh, rsh, osh = g.Sharding((M, K), (-1, -1)), g.Sharding((K, N), (-1, -1)), g.Sharding((M, N), (-1, -1))
+    n = g.dot_workspace_bytes(mesh, dims, lsh, rsh, osh, -1, False)
+    ws = torch.empty(n + 256, dtype=torch.uint8, device="cuda")
+    base = (ws.data_ptr() + 255) // 256 * 256
+    g.grouped_dot(mesh, dims, [g.ShardBuf.of(a, 0)], lsh, [g.ShardBuf.of(b, 0)], rsh, [g.ShardBuf.of(c, 0)], osh, None, base, n,
+                  torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    rows = sample_rows(M, [256, 65535, 65536, 65537, 69888], seed=9)
+    ref = od.dot_general(wl.bf16_bits_to_f64(lhs[rows]), wl.bf16_bits_to_f64(rhs), (), (), (1,), (0,))
+    got = c[torch.from_numpy(rows).cuda()].cpu().numpy().astype(np.float64)
+    assert np.array_equal(got, ref)
+    assert not torch.isnan(c).any().item()                 # every element was written
+    del c
+    torch.cuda.empty_cache()
+
+
+def test_reshard_with_more_than_2_31_elements():
+    # AllGather of a [70000, 32768] bf16 tensor (2.29e9 elements) whose rows are split two ways: the shards are the two
+    # halves of the global tensor, the gathered result must be the tensor itself, bit for bit (compared on the device)
+    import paper_2105_04663_amd as g
+    shape = (70000, 32768)
+    mesh = g.Mesh((2,), (1, 0))
+    glob = torch.randint(-32768, 32767, shape, dtype=torch.int16, device="cuda")
+    src_sh, dst_sh = g.Sharding(shape, (0, -1)), g.Sharding(shape, (-1, -1))
+    shards = []
+    for pid in range(2):
+        off, valid, shard = ob.shard_bounds((2,), (1, 0), shape, (0, -1), pid)
+        assert valid == shard == (35000, 32768)
+        shards.append(g.ShardBuf(glob[off[0]:off[0] + valid[0]].data_ptr(), g.BF16, 0))
+    dst = torch.zeros(shape, dtype=torch.int16, device="cuda")
+    n = g.reshard_workspace_bytes(mesh)
+    ws = torch.empty(n + 256, dtype=torch.uint8, device="cuda")
+    base = (ws.data_ptr() + 255) // 256 * 256
+    g.reshard(mesh, src_sh, shards, dst_sh, [g.ShardBuf(dst.data_ptr(), g.BF16, 0)] * 2, base, n, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, glob)
+    del dst, glob
+    torch.cuda.empty_cache()
