@@ -300,3 +300,23 @@ def test_reshard_with_more_than_2_31_elements():
     assert torch.equal(dst, glob)
     del dst, glob
     torch.cuda.empty_cache()
+
+
+def test_sum_of_partials_with_more_than_2_31_elements():
+    # K split two ways with a [70000, 32768] output: two 9.2 GB fp32 partials in the workspace, summed into a bf16
+    # output of 2.29e9 elements; integer operands small enough for every sum to be exact in bf16 as well
+    import paper_2105_04663_amd as g
+    M, K, N = 70000, 128, 32768
+    w = wl.ksplit(M=M, K=K, N=N, P=2)
+    lhs, rhs = wl.draw_small_int_bf16(43, (M, K), -1, 1), wl.draw_small_int_bf16(44, (K, N), -1, 1)
+    st = Staged(w, lhs, rhs, row_align=8, out_dtype="bf16")
+    st.run_grouped()
+    torch.cuda.synchronize()
+    rows = sample_rows(M, [256, 65535, 65536, 65537, 69888], seed=10)
+    ref = od.dot_general(wl.bf16_bits_to_f64(lhs[rows]), wl.bf16_bits_to_f64(rhs), (), (), (1,), (0,))
+    assert np.abs(ref).max() <= 128                        # integers up to 256 are exact in bf16
+    got = to_f64(out_tensor(st, 0)[torch.from_numpy(rows).cuda()].contiguous())
+    assert np.array_equal(got, ref)
+    assert not torch.isnan(out_tensor(st, 0)).any().item()
+    del st
+    torch.cuda.empty_cache()
