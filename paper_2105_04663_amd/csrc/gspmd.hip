@@ -613,7 +613,7 @@ int32_t gspmd_reshard_workspace_bytes(const gspmd_mesh* mesh, int64_t* bytes) {
   int64_t P = 0;
   const int32_t st = validate_mesh(mesh, &P);
   if (st != GSPMD_OK) return st;
-  *bytes = 2 * round_up(P * 8, kWsAlign) + round_up(P * static_cast<int64_t>(sizeof(ReshardDesc)), kWsAlign);
+  *bytes = round_up(P * 8, kWsAlign) + round_up(P * static_cast<int64_t>(sizeof(ReshardDesc)), kWsAlign);
   return GSPMD_OK;
 }
 
@@ -717,18 +717,16 @@ int32_t gspmd_reshard(const gspmd_mesh* mesh, const gspmd_sharding* src_sh, cons
   }
   if (descs.empty()) return GSPMD_OK;
 
-  // workspace = [device-id tensor][src pointer per partition id][descriptors]
+  // workspace = [src shard of the partition at each mesh position][descriptors]
   const int64_t ids_bytes = round_up(P * 8, kWsAlign);
-  std::vector<char> host(static_cast<size_t>(2 * ids_bytes + descs.size() * sizeof(ReshardDesc)), 0);
-  std::memcpy(host.data(), mesh->device_ids, static_cast<size_t>(P) * 8);
-  for (int64_t p = 0; p < P; ++p) std::memcpy(host.data() + ids_bytes + p * 8, &src_shards[p].data, 8);
-  std::memcpy(host.data() + 2 * ids_bytes, descs.data(), descs.size() * sizeof(ReshardDesc));
+  std::vector<char> host(static_cast<size_t>(ids_bytes + descs.size() * sizeof(ReshardDesc)), 0);
+  for (int64_t pos = 0; pos < P; ++pos) std::memcpy(host.data() + pos * 8, &src_shards[mesh->device_ids[pos]].data, 8);
+  std::memcpy(host.data() + ids_bytes, descs.data(), descs.size() * sizeof(ReshardDesc));
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   if (hipMemcpyAsync(workspace, host.data(), host.size(), hipMemcpyHostToDevice, stream) != hipSuccess) return GSPMD_ERR_DEVICE;
   const char* ws = static_cast<const char*>(workspace);
-  const int64_t* d_ids = reinterpret_cast<const int64_t*>(ws);
-  const void* const* d_ptrs = reinterpret_cast<const void* const*>(ws + ids_bytes);
-  const ReshardDesc* d_descs = reinterpret_cast<const ReshardDesc*>(ws + 2 * ids_bytes);
+  const void* const* d_ptrs = reinterpret_cast<const void* const*>(ws);
+  const ReshardDesc* d_descs = reinterpret_cast<const ReshardDesc*>(ws + ids_bytes);
 
   const int v = vec ? vec_elems : 1;
   const int64_t gx = ((max_cols + v - 1) / v + 255) / 256;
@@ -736,11 +734,11 @@ int32_t gspmd_reshard(const gspmd_mesh* mesh, const gspmd_sharding* src_sh, cons
   const int64_t gy = std::min<int64_t>(std::min<int64_t>(max_rows, 65535), std::max<int64_t>(1, 8192 / (gx * static_cast<int64_t>(descs.size()))));
   const dim3 block(256), grid(static_cast<unsigned>(gx), static_cast<unsigned>(gy), static_cast<unsigned>(descs.size()));
   if (dtype == GSPMD_BF16) {
-    if (vec) hipLaunchKernelGGL((reshard_kernel<bf16_bits, 8>), grid, block, 0, stream, d_descs, d_ids, d_ptrs);
-    else hipLaunchKernelGGL((reshard_kernel<bf16_bits, 1>), grid, block, 0, stream, d_descs, d_ids, d_ptrs);
+    if (vec) hipLaunchKernelGGL((reshard_kernel<bf16_bits, 8>), grid, block, 0, stream, d_descs, d_ptrs);
+    else hipLaunchKernelGGL((reshard_kernel<bf16_bits, 1>), grid, block, 0, stream, d_descs, d_ptrs);
   } else {
-    if (vec) hipLaunchKernelGGL((reshard_kernel<uint32_t, 4>), grid, block, 0, stream, d_descs, d_ids, d_ptrs);
-    else hipLaunchKernelGGL((reshard_kernel<uint32_t, 1>), grid, block, 0, stream, d_descs, d_ids, d_ptrs);
+    if (vec) hipLaunchKernelGGL((reshard_kernel<uint32_t, 4>), grid, block, 0, stream, d_descs, d_ptrs);
+    else hipLaunchKernelGGL((reshard_kernel<uint32_t, 1>), grid, block, 0, stream, d_descs, d_ptrs);
   }
   return hipGetLastError() == hipSuccess ? GSPMD_OK : GSPMD_ERR_DEVICE;
 }

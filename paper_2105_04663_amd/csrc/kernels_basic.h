@@ -285,10 +285,10 @@ struct ReshardDesc {              // one per distinct dst buffer
 // grid.x covers the last dimension in vectors of VEC elements, grid.y strides over rows, grid.z = dst buffer.
 // VEC > 1 needs every chunk boundary, offset and stride of the last dimension to be a multiple of VEC elements and
 // 16-byte aligned pointers (checked on the host).  The owner of an element changes only when a row crosses into
-// another src shard, so the src pointer (two dependent lookups) is fetched again only then.
+// another src shard, so the src pointer (src_by_pos[mesh position], composed on the host from the device-id tensor) is
+// fetched again only then.
 template <typename T, int VEC>
-__global__ __launch_bounds__(256) void reshard_kernel(const ReshardDesc* __restrict__ descs, const int64_t* __restrict__ ids,
-                                                      const void* const* __restrict__ src_ptrs) {
+__global__ __launch_bounds__(256) void reshard_kernel(const ReshardDesc* __restrict__ descs, const void* const* __restrict__ src_by_pos) {
   const ReshardDesc& d = descs[blockIdx.z];
   const int last = d.rank - 1;
   const int c = (blockIdx.x * blockDim.x + threadIdx.x) * VEC;
@@ -320,7 +320,7 @@ __global__ __launch_bounds__(256) void reshard_kernel(const ReshardDesc* __restr
     for (int j = 0; j < VEC; ++j) v.v[j] = T(0);
     if (ok) {
       if (pos != held_pos) {
-        src = static_cast<const T*>(src_ptrs[ids[pos]]);
+        src = static_cast<const T*>(src_by_pos[pos]);
         held_pos = pos;
       }
       if constexpr (sizeof(Vec) == 16) {
