@@ -118,8 +118,8 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const Problem* _
 #pragma unroll
       for (int j = 0; j < 4; ++j) global_to_lds16(bb, b_off[j], sa + kStageA + j * 1024);
     };
-    // a K tile that may be partial: through registers, zeroing what lies beyond the valid K in BOTH operands
-    // (executed by the four waves of group 0)
+    // one 16-byte chunk of a K tile that may be partial: into a register, zero where it lies beyond the valid K (in
+    // BOTH operands: the padding may hold anything)
     auto tail_chunk = [&](bool kmajor, const bf16_bits* base, int off, int q, int k0) -> u32x4_t {
       u32x4_t v = {0u, 0u, 0u, 0u};
       if (kmajor) {         // a whole k row per 32 lanes
