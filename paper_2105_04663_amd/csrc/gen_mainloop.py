@@ -18,7 +18,9 @@ Global->LDS tile loads (global_load_lds_dwordx4, 1 KiB per wave-instruction) are
 after every 6th MFMA and staggered by wave, so the CU's texture-address unit (about one such load per 16 cycles) sees
 an even stream and never stalls an MFMA wave; a whole tile is loaded by the four waves of ONE group: group 0 loads
 tile 2u+4 during the MFMA phase of step u, group 1 tile 2u+5.  With five stages every load has at least one full
-phase (>= 1024 cycles) plus the slack of a read phase to land.
+phase (>= 1024 cycles) plus the slack of a read phase to land.  The last two K steps have no tile left to load: they run
+a second copy of the step without loads (and without the pointer bookkeeping), so that nothing is fetched twice and the
+loop ends with no load in flight.
 The end of an MFMA phase is the loop's critical path (the other group's MFMAs wait at the barrier for it), so
 nothing but the barrier follows the last MFMA: the loads are all issued by MFMA 46, and the scalar bookkeeping of the
 phase (pointer advance, stage ring, loop counter, s_waitcnt vmcnt for the tile this barrier publishes) is spread, one
@@ -54,8 +56,7 @@ A fa_q[bm] = v[128+48q+4bm ..+3], B fb_q[bn] = v[160+48q+4bn ..+3]; v224 A read 
 addresses (per bn) in the stage being read, v229/v230 A read addresses of blocks 1..7 of a K-major lhs (an LDS read
 takes its address when it issues, so the two registers alternate).
 SGPRs: s[40:41]/s[42:43] pointers to the next A/B tile this group loads, s44 this wave's LDS write base (stage 0),
-s45 K steps left, s46 pointer advances left (the pointers stop at the last full tile: loads issued past it re-read
-that tile into a stage nobody reads any more), s47/s54 B/A pointer step in bytes (two tiles), s52 write-stage offset,
+s45 K steps left, s46 pointer advances left (the pointers stop at the last tile that is loaded), s47/s54 B/A pointer step in bytes (two tiles), s52 write-stage offset,
 s53 read-stage offset (K-major parts), s55/s56 read-stage offsets of a K-contiguous lhs/rhs, s48-s51 temporaries.
 """
 import sys
@@ -158,19 +159,19 @@ def advance():
 LOAD_STRIDE = {8: 6, 6: 4, 4: 2}      # MFMAs between two tile loads of a wave, by row blocks computed
 
 
-def mfma_phase(w, tail, nbm=8):
+def mfma_phase(w, tail, nbm=8, loads=True):
     """8 * nbm MFMAs (all 8 row blocks of the wave, or only the first nbm when the rest of its rows lies beyond the valid
-    extent).  Tile loads go after MFMAs stride * j + (wave-dependent offset), all issued 16 MFMAs before the end.
-    The pointer / stage bookkeeping and `tail` (loop counter, wait) follow, one scalar instruction after each MFMA,
-    so that nothing but the barrier comes after the last MFMA.  Only MFMAs are interleaved with the bookkeeping: it
-    passes values through SCC (compare -> select, add -> add-with-carry), which the s_add_u32 of a tile load would
-    overwrite."""
+    extent).  With `loads`, tile loads go after MFMAs stride * j + (wave-dependent offset), all issued 16 MFMAs before
+    the end, and the pointer / stage bookkeeping follows; `tail` (loop counter, wait) comes last.  All of that is spread,
+    one scalar instruction after each MFMA, over the last 16 MFMAs, so that nothing but the barrier comes after the
+    last one.  Only MFMAs are interleaved with the bookkeeping: it passes values through SCC (compare -> select,
+    add -> add-with-carry), which the s_add_u32 of a tile load would overwrite."""
     n = 8 * nbm
     st = LOAD_STRIDE[nbm]
-    load_pos = {st * j + (st * w) // 4: j for j in range(8)}
-    assert len(load_pos) == 8 and max(load_pos) < n - 16
+    load_pos = {st * j + (st * w) // 4: j for j in range(8)} if loads else {}
+    assert not loads or (len(load_pos) == 8 and max(load_pos) < n - 16)
     out = []
-    adv = advance() + tail
+    adv = (advance() if loads else []) + tail
     assert len(adv) <= 15
     i = 0
     for q in range(2):
@@ -187,21 +188,31 @@ def mfma_phase(w, tail, nbm=8):
 
 
 def group0(w, layout):
-    """Waves 0-3: read phase of K step u, barrier, MFMA phase of u (loading tile 2u+4), barrier."""
-    s = ["L0_top_%=:"] + mem_phase(layout) + ["s_add_u32 s49, s44, s52", "s_waitcnt lgkmcnt(0)", "s_barrier"]
+    """Waves 0-3: read phase of K step u, barrier, MFMA phase of u, barrier.  Tile 2u+4 is loaded during the MFMA phase
+    of step u; the last two steps have no tile left to load and run a copy of the step without loads (its wait is for
+    everything still in flight: the first tile of the last step)."""
+    s = ["s_cmp_le_u32 s45, 2", "s_cbranch_scc1 L0_drain_%="]
+    s += ["L0_top_%=:"] + mem_phase(layout) + ["s_add_u32 s49, s44, s52", "s_waitcnt lgkmcnt(0)", "s_barrier"]
     s += mfma_phase(w, ["s_sub_u32 s45, s45, 1", "s_waitcnt vmcnt(8)"])
-    s += ["s_barrier", "s_cmp_lg_u32 s45, 0", "s_cbranch_scc1 L0_top_%=", "s_nop 15", "s_nop 15"]
+    s += ["s_barrier", "s_cmp_gt_u32 s45, 2", "s_cbranch_scc1 L0_top_%="]
+    s += ["L0_drain_%=:"] + mem_phase(layout) + ["s_waitcnt lgkmcnt(0)", "s_barrier"]
+    s += mfma_phase(w, ["s_sub_u32 s45, s45, 1", "s_waitcnt vmcnt(0)"], loads=False)
+    s += ["s_barrier", "s_cmp_lg_u32 s45, 0", "s_cbranch_scc1 L0_drain_%=", "s_nop 15", "s_nop 15"]
     return s
 
 
 def group1(w, layout, nbm=8):
-    """Waves 4-7: one phase behind group 0 (extra barrier first); loads tile 2u+5 in its MFMA phase.  nbm < 8: the
-    variant for an output tile whose valid rows end inside this group's half (rows 128-255): only the first nbm
-    16-row blocks are read and multiplied."""
-    s = ["s_barrier", "L1_top_%=:"] + mem_phase(layout, nbm) + ["s_add_u32 s49, s44, s52", "s_waitcnt vmcnt(0) lgkmcnt(0)", "s_barrier"]
+    """Waves 4-7: one phase behind group 0 (extra barrier first); loads tile 2u+5 in the MFMA phase of step u, nothing in
+    the last two steps.  nbm < 8: the variant for an output tile whose valid rows end inside this group's half (rows
+    128-255): only the first nbm 16-row blocks are read and multiplied."""
+    s = ["s_barrier", "s_cmp_le_u32 s45, 2", "s_cbranch_scc1 L1_drain_%="]
+    s += ["L1_top_%=:"] + mem_phase(layout, nbm) + ["s_add_u32 s49, s44, s52", "s_waitcnt vmcnt(0) lgkmcnt(0)", "s_barrier"]
     s += mfma_phase(w, ["s_sub_u32 s45, s45, 1"], nbm)
+    s += ["s_barrier", "s_cmp_gt_u32 s45, 2", "s_cbranch_scc1 L1_top_%="]
+    s += ["L1_drain_%=:"] + mem_phase(layout, nbm) + ["s_waitcnt vmcnt(0) lgkmcnt(0)", "s_barrier"]
+    s += mfma_phase(w, ["s_sub_u32 s45, s45, 1"], nbm, loads=False)
     s += ["s_cmp_lg_u32 s45, 0", "s_cbranch_scc0 L1_end_%=",
-          "s_barrier", "s_branch L1_top_%=", "L1_end_%=:", "s_nop 15", "s_nop 15"]
+          "s_barrier", "s_branch L1_drain_%=", "L1_end_%=:", "s_nop 15", "s_nop 15"]
     return s
 
 

@@ -88,6 +88,10 @@ def trace(lines, sgpr, outstanding):
             scc = int(val(a[0]) != val(a[1]))
         elif op == "s_cmp_ge_u32":
             scc = int(val(a[0]) >= val(a[1]))
+        elif op == "s_cmp_gt_u32":
+            scc = int(val(a[0]) > val(a[1]))
+        elif op == "s_cmp_le_u32":
+            scc = int(val(a[0]) <= val(a[1]))
         elif op == "s_cselect_b32":
             s[a[0]] = val(a[1]) if scc else val(a[2])
         elif op == "s_cbranch_scc1":

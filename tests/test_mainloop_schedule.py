@@ -1,8 +1,8 @@
 """CPU checks of the generated assembly main loop (csrc/gen_mainloop.py -> csrc/mainloop_asm.h).
 
 The loop's scalar bookkeeping (tile pointers, LDS stage ring, loop counter) is executed in a small SALU interpreter
-and compared with closed forms: which tile every load instruction fetches, where in LDS it lands, that the pointers
-never move past the loop's last tile (the bug class that reads out of bounds), and that the two wave groups execute
+and compared with closed forms: which tile every load instruction fetches, where in LDS it lands, that no load is
+issued for a tile past the loop's last one (the bug class that reads out of bounds), and that the two wave groups execute
 the same number of barriers (the bug class that hangs).  Also: the committed header is what the generator writes."""
 import importlib.util
 import os
@@ -70,6 +70,10 @@ def run(lines, sgpr):
             scc = int(val(a[0]) != val(a[1]))
         elif op == "s_cmp_ge_u32":
             scc = int(val(a[0]) >= val(a[1]))
+        elif op == "s_cmp_gt_u32":
+            scc = int(val(a[0]) > val(a[1]))
+        elif op == "s_cmp_le_u32":
+            scc = int(val(a[0]) <= val(a[1]))
         elif op == "s_cselect_b32":
             s[a[0]] = val(a[1]) if scc else val(a[2])
         elif op == "s_cbranch_scc1":
@@ -105,14 +109,16 @@ def test_tile_loads_land_where_the_kernel_reads_them_and_stay_in_bounds(layout, 
         for nk64 in (1, 2, 3, 4, 5, 9, 16):
             sg, a0, b0 = initial(grp, w, nk64)
             lines = g.group0(w, layout) if grp == 0 else g.group1(w, layout, nbm)
-            assert sum(l.startswith("v_mfma") for l in lines) == 8 * nbm
+            assert sum(l.startswith("v_mfma") for l in lines) == 2 * 8 * nbm     # the step with loads and its copy without
             ev, end = run(lines, sg)
             loads = [e for e in ev if e[0] == "load"]
-            assert len(loads) == 8 * nk64                     # one tile (8 instructions of this wave) per K step
+            nload = max(nk64 - 2, 0)                          # the last two steps have no tile left to load
+            assert len(loads) == 8 * nload                    # one tile (8 instructions of this wave) per loading step
             nadv = sg["s46"]
-            for u in range(nk64):
+            assert nadv == max(nload - 1, 0)                  # so the pointers never move past the last tile loaded
+            for u in range(nload):
                 step_loads = loads[8 * u:8 * u + 8]
-                adv = min(u, nadv)                             # pointers freeze at the loop's last tile
+                adv = min(u, nadv)
                 stage = ((4 + grp + 2 * u) % NSTAGE) * STAGE
                 want = set()
                 for j in range(4):
