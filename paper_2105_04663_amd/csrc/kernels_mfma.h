@@ -259,7 +259,11 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const Problem* _
     {
       u32x4_t ta[4], tb[4];
       if (wm < ntail) fetch_tail(nkt + wm, ta, tb);
-      if (nk64 > 0) {
+      // Without leftover tiles nothing follows the loop but the epilogue, and that needs no barrier: the loop ends with
+      // no tile load in flight, and every wave's last LDS read was complete before the last barrier that both groups
+      // passed, so a wave may overwrite LDS (its epilogue's staging slice) as soon as its own MFMAs are done -- group 0
+      // a phase before group 1.
+      if (nk64 > 0 && ntail > 0) {
         GSPMD_WAIT_ALL();
         __syncthreads();
       }
@@ -284,7 +288,7 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const Problem* _
     // tile wholly inside the valid region: no predicates; bf16 through the hardware round-to-nearest-even conversion
     if constexpr (sizeof(TOut) == 2) {
       // bf16: the wave's 128 x 64 block is a 128-byte line per row, but a lane holds only 8 bytes of it per 16-column
-      // block.  Stage it through the wave's own slice of LDS (free now: every wave is past the loop's last barrier;
+      // block.  Stage it through the wave's own slice of LDS (free now: every wave's LDS reads are over and no tile load is in flight;
       // rows padded to 144 bytes against bank conflicts) and store 16 bytes per lane, 8 lanes per row: whole lines.
       constexpr int kPitch = 144;
       unsigned char* slice = smem + wave * (128 * kPitch);

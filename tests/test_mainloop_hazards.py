@@ -10,7 +10,9 @@ variant):
     held before;
   * a wave reaches a barrier with no LDS read outstanding (the fragments are in registers before the MFMAs start, and
     the reads of a stage are over before the barrier that frees it);
-  * every read goes to the stage of the tile it is meant to read.
+  * every read goes to the stage of the tile it is meant to read;
+  * a wave leaves the loop with no tile load in flight and with its last LDS read before the last barrier both groups
+    pass (the kernel's epilogue reuses LDS without a further barrier).
 The model cannot see timing, only what the waits and barriers guarantee."""
 import re
 
@@ -123,6 +125,10 @@ def test_waits_and_barriers_order_every_tile_load_and_read(layout, nbm, nk64):
             # in flight at loop start: this wave's 8 pieces of tile 2 (group 0) or 3 (group 1), serials 0-7
             ev, left, last_epoch = trace(lines, sg, range(8))
             epochs.add(last_epoch)
+            assert not left, "a tile load is still in flight when the wave leaves the loop"
+            # the wave's last LDS read lies before the last barrier it shares with the other group (group 1 passes no
+            # barrier after its last MFMA phase), so LDS may be reused right after the loop without another barrier
+            assert max(e[1] for e in ev if e[0] == "read") < 2 * nk64
             batch_of = {}                     # load serial -> tile
             nload = 0
             for e in ev:
