@@ -25,8 +25,8 @@ import numpy as np
 PEAK_BF16_TFLOPS = 2516.6   # 256 CU x 4096 flop/clk/CU x 2.4 GHz (dense bf16 MFMA)
 PEAK_HBM_GBS = 8000.0
 # L2 <-> fabric bytes of one dot_mfma_kernel launch on the FFN share, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled
-# by a copy kernel of known size (profiles/dot_mfma_kernel_ffn_share.md): 3.222e9 fetched + 0.268e9 written
-FFN_TRAFFIC_BYTES = 3.222e9 + 0.268e9
+# by a copy kernel of known size (profiles/dot_mfma_kernel_ffn_share.md): 3.224e9 fetched + 0.268e9 written
+FFN_TRAFFIC_BYTES = 3.224e9 + 0.268e9
 METRIC = "per-shard einsum bf16 TFLOP/s and % of MI355X MFMA peak (1 GPU)"
 
 
