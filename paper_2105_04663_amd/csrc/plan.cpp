@@ -80,11 +80,6 @@ int32_t shard_bounds(const gspmd_mesh* mesh, const gspmd_sharding* sh, int64_t p
 
 namespace {
 
-bool in_list(const int* list, int n, int v) {
-  for (int i = 0; i < n; ++i) if (list[i] == v) return true;
-  return false;
-}
-
 int find_axis_dim(const gspmd_sharding* sh, int axis) {
   for (int i = 0; i < sh->rank; ++i) if (sh->dims_mapping[i] == axis) return i;
   return -1;
