@@ -51,16 +51,24 @@ def sample_clock_under_load(step, torch, seconds=1.5):
     timed region): the kernel is power-limited, so the clock the data allows is part of the result.  None if rocm-smi
     is missing or prints something else."""
     import re
+    import shutil
     import subprocess
     import threading
+    # Not under a profiler: its preloaded library would initialise the GPU in every child process, and rocm-smi is a
+    # script that re-executes an interpreter.  The script is run with this interpreter directly for the same reason.
+    if any("rocprof" in os.environ.get(k, "").lower() for k in ("LD_PRELOAD", "ROCP_TOOL_LIBRARIES", "ROCPROFILER_LIBRARY_CTOR")):
+        return None
+    smi = shutil.which("rocm-smi")
+    if smi is None:
+        return None
     samples, done = [], threading.Event()
 
     def sampler():
         time.sleep(0.4)
         while not done.is_set():
             try:
-                out = subprocess.run(["rocm-smi", "--showclocks", "--showpower", "--json"], capture_output=True, text=True,
-                                     timeout=10).stdout
+                out = subprocess.run([sys.executable, smi, "--showclocks", "--showpower", "--json"], capture_output=True,
+                                     text=True, timeout=10).stdout
                 card = json.loads(out)
                 card = card[sorted(card)[0]]
                 entry = {}
