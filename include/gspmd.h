@@ -15,16 +15,22 @@
  *     library never allocates or frees device memory.
  *   - Device work is enqueued on the given hipStream_t (passed as void*; NULL
  *     is the default stream) and is complete when that stream is.
- *   - Every function returns a gspmd_status and never throws, aborts or prints.
- *     Outputs are written only on GSPMD_OK.
- *   - The library keeps no state between calls; independent calls may be made from several
- *     host threads.  Calls that launch kernels upload small launch tables from a temporary host
- *     buffer with a stream-ordered copy, so they must not be recorded into a HIP graph.
- *   - Tensors are row-major.  A shard buffer has the STATIC shard shape
- *     (ceil(D/n) per split dimension, Section 4.1), whatever the partition's
- *     valid length; the library reads no element at an index >= the valid
- *     length of any dimension (padding may hold anything, including NaN) and
- *     writes zeros to the padded part of outputs.
+ *   - Every function returns a gspmd_status and never throws (a failed host allocation comes back as
+ *     GSPMD_ERR_HOST_MEMORY), aborts or prints.  Outputs are written only on GSPMD_OK.
+ *   - The library keeps no state between calls (gspmd_grouped_dot_noalloc's static workspace aside); independent
+ *     calls may be made from several host threads.
+ *   - HIP graphs: a kernel-launching call whose launch tables fit its kernels' arguments enqueues kernels only and
+ *     may be recorded into a graph: a Dot lowered to at most 32 GEMM problems (every benchmark configuration; the
+ *     count is what gspmd_plan_dot reports, summed over the partitions of a grouped call), a resharding on a mesh of
+ *     at most 64 partitions with at most 8 distinct destination buffers.  Beyond that the tables are uploaded into
+ *     the workspace with a stream-ordered copy from a temporary host buffer, and such a call must not be recorded.
+ *   - Tensors are row-major.  A shard buffer has the STATIC shard shape (ceil(D/n) per split dimension,
+ *     Section 4.1), whatever the partition's valid length.  Padding may hold anything, including NaN: no value at
+ *     an index >= the valid length of any dimension reaches a result.  Reads stay inside the rows of the valid
+ *     region: the MFMA kernels load 16 bytes at a time, so when a row's valid length is not a multiple of 8 elements
+ *     the chunk that holds its last valid elements is loaded whole (from inside the row's own allocation, which the
+ *     required row stride of a multiple of 8 elements guarantees) and the excess is discarded or zeroed in
+ *     registers.  The padded part of outputs is written as zeros.
  */
 #ifndef GSPMD_H_
 #define GSPMD_H_
@@ -38,7 +44,7 @@ extern "C" {
 typedef enum {
   GSPMD_OK = 0,
   GSPMD_ERR_NULL = 1,            /* a required pointer is NULL */
-  GSPMD_ERR_BAD_MESH = 2,        /* rank/size <= 0, ids not a permutation of 0..P-1 */
+  GSPMD_ERR_BAD_MESH = 2,        /* rank/size <= 0, more than 2^20 partitions, ids not a permutation of 0..P-1 */
   GSPMD_ERR_BAD_SHARDING = 3,    /* rank mismatch, mesh dim out of range or used twice (Section 3.1) */
   GSPMD_ERR_PARTITION_RANGE = 4, /* partition id not in the mesh */
   GSPMD_ERR_BAD_DOT_DIMS = 5,    /* duplicate/out-of-range dims, size mismatch, wrong output shape */
@@ -46,7 +52,8 @@ typedef enum {
   GSPMD_ERR_UNSUPPORTED = 7,     /* dtype/layout combination not implemented */
   GSPMD_ERR_WORKSPACE = 8,       /* workspace missing, misaligned or too small */
   GSPMD_ERR_DEVICE = 9,          /* a HIP call failed */
-  GSPMD_ERR_BAD_BUFFER = 10      /* row_stride smaller than the shard's last dimension, bad fill count */
+  GSPMD_ERR_BAD_BUFFER = 10,     /* row_stride smaller than the shard's last dimension, bad fill count */
+  GSPMD_ERR_HOST_MEMORY = 11     /* a host-side allocation failed */
 } gspmd_status;
 
 typedef enum { GSPMD_F32 = 0, GSPMD_BF16 = 1 } gspmd_dtype;
@@ -112,6 +119,7 @@ typedef struct {
   int64_t row_stride;  /* elements; 0 = dense */
 } gspmd_shard_buf;
 
+/* Utility (no counterpart in the paper): a short English name for a gspmd_status; never NULL. */
 const char* gspmd_status_string(int32_t status);
 
 /* Offset(S, d, i) of Section 3.5 with the static shard size of Section 4.1.
@@ -162,7 +170,8 @@ typedef struct {
   int32_t layout;
 } gspmd_gemm_desc;
 
-/* How gspmd_local_dot lowers partition `partition_id`'s Dot (shard bounds -> flattened batch / free / contracting
+/* Utility for inspection and tests: the per-partition program of Section 4 made explicit.
+ * How gspmd_local_dot lowers partition `partition_id`'s Dot (shard bounds -> flattened batch / free / contracting
  * extents -> one GEMM per batch entry and per index of a free dimension that padding keeps from flattening), without
  * touching the GPU.  *_row_stride as in gspmd_shard_buf: 0 = dense.  Writes min(count, capacity) descriptors to
  * `descs` (may be NULL when capacity is 0) and the total to `count`.  Pure host work; for inspection and tests. */
@@ -172,7 +181,8 @@ int32_t gspmd_plan_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
                        int64_t partition_id, const int64_t* lhs_fill,
                        gspmd_gemm_desc* descs, int64_t capacity, int64_t* count);
 
-/* Bytes of device workspace gspmd_local_dot (partition_id >= 0) or gspmd_grouped_dot
+/* Utility (the library allocates nothing, so the caller sizes the workspace):
+ * bytes of device workspace gspmd_local_dot (partition_id >= 0) or gspmd_grouped_dot
  * (partition_id = -1: all partitions) needs for these arguments.  `has_fill` says whether a
  * fill-count array will be passed.  Pure host work. */
 int32_t gspmd_dot_workspace_bytes(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
@@ -249,7 +259,7 @@ int32_t gspmd_shard_assemble(const gspmd_mesh* mesh, const gspmd_sharding* shard
                              int64_t partition_id, const gspmd_shard_buf* shard,
                              void* global_data, void* hip_stream);
 
-/* Bytes of device workspace gspmd_reshard needs on this mesh.  Pure host work. */
+/* Utility: bytes of device workspace gspmd_reshard needs on this mesh.  Pure host work. */
 int32_t gspmd_reshard_workspace_bytes(const gspmd_mesh* mesh, int64_t* bytes);
 
 /* Resharding on the virtual mesh (Section 4.5): rewrite a tensor held under sharding `src_sh` into shard buffers under

@@ -58,10 +58,12 @@ bool mfma_eligible(const std::vector<Problem>& ps, int32_t in_dtype, int32_t lay
   return true;
 }
 
-// Upload the launch tables into the workspace and run the contraction over all live tiles, then the zero fill of
-// what the tiles do not cover.  Output tiles cover the valid extents only (rounded up to whole tiles, the kernel
-// writes zeros inside a partly valid tile): tiles that would only write zeros are not interleaved with live ones,
-// which would leave compute units idle (workgroups are placed in order), and cost no workgroup launches.
+// Run the contraction over all live tiles, then the zero fill of what the tiles do not cover.  Output tiles cover
+// the valid extents only (rounded up to whole tiles, the kernel writes zeros inside a partly valid tile): tiles that
+// would only write zeros are not interleaved with live ones, which would leave compute units idle (workgroups are
+// placed in order), and cost no workgroup launches.  Tables of up to kInlineProblems problems and kInlineRects
+// rectangles travel as kernel arguments; larger ones are uploaded into the workspace with a stream-ordered copy from
+// a temporary host buffer (HIP stages a pageable source before the call returns).
 int32_t launch_problems(std::vector<Problem>& all, int32_t layout, int32_t in_dtype, int32_t out_dtype, int32_t epilogue,
                         void* workspace, int64_t workspace_bytes, hipStream_t stream) {
   // problems with an empty static output block write nothing
@@ -81,33 +83,45 @@ int32_t launch_problems(std::vector<Problem>& all, int32_t layout, int32_t in_dt
     if (rows_done < p.Ms) rects.push_back(ZeroRect{p.C, p.ldc, rows_done, p.Ms, 0, p.Ns, 0});
     if (cols_done < p.Ns && rows_done > 0) rects.push_back(ZeroRect{p.C, p.ldc, 0, rows_done, cols_done, p.Ns, 0});
   }
+  const bool inline_tables = ps.size() <= static_cast<size_t>(kInlineProblems) && rects.size() <= static_cast<size_t>(kInlineRects);
   const int64_t prob_bytes = static_cast<int64_t>(ps.size()) * sizeof(Problem);
-  const int64_t table_bytes = prob_bytes + static_cast<int64_t>(rects.size()) * sizeof(ZeroRect);
-  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kWsAlign - 1)) || workspace_bytes < table_bytes)
-    return GSPMD_ERR_WORKSPACE;
-  std::vector<char> host(static_cast<size_t>(table_bytes));
-  if (prob_bytes) std::memcpy(host.data(), ps.data(), static_cast<size_t>(prob_bytes));
-  if (!rects.empty()) std::memcpy(host.data() + prob_bytes, rects.data(), rects.size() * sizeof(ZeroRect));
-  if (hipMemcpyAsync(workspace, host.data(), host.size(), hipMemcpyHostToDevice, stream) != hipSuccess)
-    return GSPMD_ERR_DEVICE;
-  const Problem* tab = static_cast<const Problem*>(workspace);
+  const Problem* tab = nullptr;
+  const ZeroRect* drects = nullptr;
+  InlineProblems inl;
+  InlineRects inl_rects;
+  std::memset(&inl, 0, sizeof(inl));
+  std::memset(&inl_rects, 0, sizeof(inl_rects));
+  if (inline_tables) {
+    if (!ps.empty()) std::memcpy(inl.p, ps.data(), static_cast<size_t>(prob_bytes));
+    if (!rects.empty()) std::memcpy(inl_rects.r, rects.data(), rects.size() * sizeof(ZeroRect));
+  } else {
+    const int64_t table_bytes = prob_bytes + static_cast<int64_t>(rects.size()) * sizeof(ZeroRect);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kWsAlign - 1)) || workspace_bytes < table_bytes)
+      return GSPMD_ERR_WORKSPACE;
+    std::vector<char> host(static_cast<size_t>(table_bytes));
+    if (prob_bytes) std::memcpy(host.data(), ps.data(), static_cast<size_t>(prob_bytes));
+    if (!rects.empty()) std::memcpy(host.data() + prob_bytes, rects.data(), rects.size() * sizeof(ZeroRect));
+    if (hipMemcpyAsync(workspace, host.data(), host.size(), hipMemcpyHostToDevice, stream) != hipSuccess)
+      return GSPMD_ERR_DEVICE;
+    tab = static_cast<const Problem*>(workspace);
+    drects = reinterpret_cast<const ZeroRect*>(static_cast<const char*>(workspace) + prob_bytes);
+  }
   const int n = static_cast<int>(ps.size());
   if (tiles > 0) {
     if (mfma) {
-      if (!launch_dot_mfma(tab, n, static_cast<int>(tiles), layout, out_dtype, epilogue, stream)) return GSPMD_ERR_DEVICE;
+      if (!launch_dot_mfma(inl, tab, n, static_cast<int>(tiles), layout, out_dtype, epilogue, stream)) return GSPMD_ERR_DEVICE;
     } else {
       const dim3 grid(static_cast<unsigned>(tiles)), block(256);
       if (in_dtype == GSPMD_F32)
-        hipLaunchKernelGGL((dot_fallback_kernel<float, float>), grid, block, 0, stream, tab, n, layout, epilogue);
+        hipLaunchKernelGGL((dot_fallback_kernel<float, float>), grid, block, 0, stream, inl, tab, n, layout, epilogue);
       else if (out_dtype == GSPMD_F32)
-        hipLaunchKernelGGL((dot_fallback_kernel<bf16_bits, float>), grid, block, 0, stream, tab, n, layout, epilogue);
+        hipLaunchKernelGGL((dot_fallback_kernel<bf16_bits, float>), grid, block, 0, stream, inl, tab, n, layout, epilogue);
       else
-        hipLaunchKernelGGL((dot_fallback_kernel<bf16_bits, bf16_bits>), grid, block, 0, stream, tab, n, layout, epilogue);
+        hipLaunchKernelGGL((dot_fallback_kernel<bf16_bits, bf16_bits>), grid, block, 0, stream, inl, tab, n, layout, epilogue);
       if (hipGetLastError() != hipSuccess) return GSPMD_ERR_DEVICE;
     }
   }
   if (!rects.empty()) {
-    const ZeroRect* drects = reinterpret_cast<const ZeroRect*>(static_cast<const char*>(workspace) + prob_bytes);
     const int vec_elems = out_dtype == GSPMD_F32 ? 4 : 8;
     bool vec = true;
     int64_t most = 0;
@@ -121,13 +135,13 @@ int32_t launch_problems(std::vector<Problem>& all, int32_t layout, int32_t in_dt
     for (size_t first = 0; first < rects.size(); first += 65535) {       // grid.y is limited to 65535
       const unsigned gy = static_cast<unsigned>(std::min<size_t>(rects.size() - first, 65535));
       const dim3 grid(gx, gy), block(256);
-      const ZeroRect* part = drects + first;
+      const ZeroRect* part = drects ? drects + first : nullptr;
       if (out_dtype == GSPMD_F32) {
-        if (vec) hipLaunchKernelGGL((zero_rects_kernel<float, 4>), grid, block, 0, stream, part);
-        else hipLaunchKernelGGL((zero_rects_kernel<float, 1>), grid, block, 0, stream, part);
+        if (vec) hipLaunchKernelGGL((zero_rects_kernel<float, 4>), grid, block, 0, stream, inl_rects, part);
+        else hipLaunchKernelGGL((zero_rects_kernel<float, 1>), grid, block, 0, stream, inl_rects, part);
       } else {
-        if (vec) hipLaunchKernelGGL((zero_rects_kernel<bf16_bits, 8>), grid, block, 0, stream, part);
-        else hipLaunchKernelGGL((zero_rects_kernel<bf16_bits, 1>), grid, block, 0, stream, part);
+        if (vec) hipLaunchKernelGGL((zero_rects_kernel<bf16_bits, 8>), grid, block, 0, stream, inl_rects, part);
+        else hipLaunchKernelGGL((zero_rects_kernel<bf16_bits, 1>), grid, block, 0, stream, inl_rects, part);
       }
     }
     if (hipGetLastError() != hipSuccess) return GSPMD_ERR_DEVICE;
@@ -249,12 +263,13 @@ const char* gspmd_status_string(int32_t s) {
     case GSPMD_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case GSPMD_ERR_DEVICE: return "HIP error";
     case GSPMD_ERR_BAD_BUFFER: return "bad shard buffer";
+    case GSPMD_ERR_HOST_MEMORY: return "host allocation failed";
     default: return "unknown status";
   }
 }
 
 int32_t gspmd_shard_bounds(const gspmd_mesh* mesh, const gspmd_sharding* sh, int64_t pid,
-                           int64_t* offset, int64_t* valid_len, int64_t* shard_size) {
+                           int64_t* offset, int64_t* valid_len, int64_t* shard_size) try {
   if (!offset || !valid_len) return GSPMD_ERR_NULL;
   int32_t st = validate_mesh(mesh, nullptr);
   if (st != GSPMD_OK) return st;
@@ -267,11 +282,11 @@ int32_t gspmd_shard_bounds(const gspmd_mesh* mesh, const gspmd_sharding* sh, int
     if (shard_size) shard_size[i] = b.shard[i];
   }
   return GSPMD_OK;
-}
+} catch (...) { return GSPMD_ERR_HOST_MEMORY; }
 
 int32_t gspmd_classify_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
                            const gspmd_sharding* lhs_sh, const gspmd_sharding* rhs_sh,
-                           const gspmd_sharding* out_sh, int32_t* axis_class) {
+                           const gspmd_sharding* out_sh, int32_t* axis_class) try {
   if (!axis_class) return GSPMD_ERR_NULL;
   DotRoles r;
   int32_t cls[kMaxRank];
@@ -279,11 +294,11 @@ int32_t gspmd_classify_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
   if (st != GSPMD_OK) return st;
   for (int a = 0; a < mesh->rank; ++a) axis_class[a] = cls[a];
   return GSPMD_OK;
-}
+} catch (...) { return GSPMD_ERR_HOST_MEMORY; }
 
 int32_t gspmd_infer_out_sharding(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
                                  const gspmd_sharding* lhs_sh, const gspmd_sharding* rhs_sh,
-                                 int32_t* out_mapping, int64_t* out_shape, int32_t* out_rank) {
+                                 int32_t* out_mapping, int64_t* out_shape, int32_t* out_rank) try {
   if (!out_mapping || !dims) return GSPMD_ERR_NULL;
   int32_t st = validate_mesh(mesh, nullptr);
   if (st != GSPMD_OK) return st;
@@ -345,13 +360,13 @@ int32_t gspmd_infer_out_sharding(const gspmd_mesh* mesh, const gspmd_dot_dims* d
   for (int i = 0; i < rank; ++i) { out_mapping[i] = map[i]; if (out_shape) out_shape[i] = shape[i]; }
   if (out_rank) *out_rank = rank;
   return GSPMD_OK;
-}
+} catch (...) { return GSPMD_ERR_HOST_MEMORY; }
 
 int32_t gspmd_plan_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
                        const gspmd_sharding* lhs_sh, const gspmd_sharding* rhs_sh, const gspmd_sharding* out_sh,
                        int64_t lhs_row_stride, int64_t rhs_row_stride, int64_t out_row_stride,
                        int64_t pid, const int64_t* lhs_fill,
-                       gspmd_gemm_desc* descs, int64_t capacity, int64_t* count) {
+                       gspmd_gemm_desc* descs, int64_t capacity, int64_t* count) try {
   if (!count || (capacity > 0 && !descs)) return GSPMD_ERR_NULL;
   if (capacity < 0 || lhs_row_stride < 0 || rhs_row_stride < 0 || out_row_stride < 0) return GSPMD_ERR_BAD_BUFFER;
   DotRoles r;
@@ -380,12 +395,12 @@ int32_t gspmd_plan_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
     d.layout = layout;
   }
   return GSPMD_OK;
-}
+} catch (...) { return GSPMD_ERR_HOST_MEMORY; }
 
 int32_t gspmd_dot_workspace_bytes(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
                                   const gspmd_sharding* lhs_sh, const gspmd_sharding* rhs_sh,
                                   const gspmd_sharding* out_sh, int64_t pid, int32_t /*has_fill*/,
-                                  int64_t* bytes) {
+                                  int64_t* bytes) try {
   if (!bytes) return GSPMD_ERR_NULL;
   DotRoles r;
   int32_t cls[kMaxRank];
@@ -407,14 +422,14 @@ int32_t gspmd_dot_workspace_bytes(const gspmd_mesh* mesh, const gspmd_dot_dims* 
   }
   *bytes = round_up(std::max<int64_t>(n_prob, 1) * kTableBytesPerProblem, kWsAlign) + partial_bytes;
   return GSPMD_OK;
-}
+} catch (...) { return GSPMD_ERR_HOST_MEMORY; }
 
 int32_t gspmd_local_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
                         const gspmd_shard_buf* lhs, const gspmd_sharding* lhs_sh,
                         const gspmd_shard_buf* rhs, const gspmd_sharding* rhs_sh,
                         const gspmd_shard_buf* out, const gspmd_sharding* out_sh,
                         int64_t pid, const int64_t* lhs_fill, int32_t epilogue,
-                        void* workspace, int64_t workspace_bytes, void* hip_stream) {
+                        void* workspace, int64_t workspace_bytes, void* hip_stream) try {
   int32_t st;
   if (!is_epilogue(epilogue)) return GSPMD_ERR_UNSUPPORTED;
   if ((st = check_buf(lhs)) != GSPMD_OK || (st = check_buf(rhs)) != GSPMD_OK || (st = check_buf(out)) != GSPMD_OK) return st;
@@ -432,14 +447,14 @@ int32_t gspmd_local_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
   for (const auto& p : ps)
     if ((p.Kv && (!p.A || !p.B)) || !p.C) return GSPMD_ERR_NULL;
   return launch_problems(ps, layout, lhs->dtype, out->dtype, epilogue, workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
-}
+} catch (...) { return GSPMD_ERR_HOST_MEMORY; }
 
 int32_t gspmd_grouped_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
                           const gspmd_shard_buf* lhs_shards, const gspmd_sharding* lhs_sh,
                           const gspmd_shard_buf* rhs_shards, const gspmd_sharding* rhs_sh,
                           const gspmd_shard_buf* out_shards, const gspmd_sharding* out_sh,
                           const int64_t* lhs_fill, int32_t epilogue,
-                          void* workspace, int64_t workspace_bytes, void* hip_stream) {
+                          void* workspace, int64_t workspace_bytes, void* hip_stream) try {
   if (!lhs_shards || !rhs_shards || !out_shards) return GSPMD_ERR_NULL;
   if (!is_epilogue(epilogue)) return GSPMD_ERR_UNSUPPORTED;
   DotRoles r;
@@ -536,20 +551,20 @@ int32_t gspmd_grouped_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
     }
   }
   return GSPMD_OK;
-}
+} catch (...) { return GSPMD_ERR_HOST_MEMORY; }
 
 int32_t gspmd_reduce_partials(const void* const* partials, int32_t n_partials, int64_t n_elems,
-                              void* out, int32_t out_dtype, void* hip_stream) {
+                              void* out, int32_t out_dtype, void* hip_stream) try {
   if (!partials || !out) return GSPMD_ERR_NULL;
   if (n_partials < 1 || n_partials > kMaxPartials || n_elems < 0) return GSPMD_ERR_BAD_BUFFER;
   if (!is_dtype(out_dtype)) return GSPMD_ERR_UNSUPPORTED;
   for (int i = 0; i < n_partials; ++i) if (!partials[i]) return GSPMD_ERR_NULL;
   return launch_reduce(reinterpret_cast<const float* const*>(partials), n_partials, 1, n_elems, n_elems, out, n_elems,
                        out_dtype, static_cast<hipStream_t>(hip_stream));
-}
+} catch (...) { return GSPMD_ERR_HOST_MEMORY; }
 
 static int32_t shard_copy(const gspmd_mesh* mesh, const gspmd_sharding* sh, int64_t pid, const void* src_global,
-                          void* dst_global, const gspmd_shard_buf* shard, uint32_t pad_bits, bool extract, void* hip_stream) {
+                          void* dst_global, const gspmd_shard_buf* shard, uint32_t pad_bits, bool extract, void* hip_stream) try {
   int32_t st = validate_mesh(mesh, nullptr);
   if (st != GSPMD_OK) return st;
   if ((st = validate_sharding(mesh, sh)) != GSPMD_OK) return st;
@@ -596,30 +611,30 @@ static int32_t shard_copy(const gspmd_mesh* mesh, const gspmd_sharding* sh, int6
     else hipLaunchKernelGGL((shard_copy_kernel<T, false>), grid, block, 0, stream, d, static_cast<const T*>(shard->data), static_cast<T*>(dst_global) + goff, 0u, total);
   }
   return hipGetLastError() == hipSuccess ? GSPMD_OK : GSPMD_ERR_DEVICE;
-}
+} catch (...) { return GSPMD_ERR_HOST_MEMORY; }
 
 int32_t gspmd_shard_extract(const gspmd_mesh* mesh, const gspmd_sharding* sh, int64_t pid, const void* global_data,
-                            const gspmd_shard_buf* shard, uint32_t pad_bits, void* hip_stream) {
+                            const gspmd_shard_buf* shard, uint32_t pad_bits, void* hip_stream) try {
   return shard_copy(mesh, sh, pid, global_data, nullptr, shard, pad_bits, true, hip_stream);
-}
+} catch (...) { return GSPMD_ERR_HOST_MEMORY; }
 
 int32_t gspmd_shard_assemble(const gspmd_mesh* mesh, const gspmd_sharding* sh, int64_t pid, const gspmd_shard_buf* shard,
-                             void* global_data, void* hip_stream) {
+                             void* global_data, void* hip_stream) try {
   return shard_copy(mesh, sh, pid, nullptr, global_data, shard, 0, false, hip_stream);
-}
+} catch (...) { return GSPMD_ERR_HOST_MEMORY; }
 
-int32_t gspmd_reshard_workspace_bytes(const gspmd_mesh* mesh, int64_t* bytes) {
+int32_t gspmd_reshard_workspace_bytes(const gspmd_mesh* mesh, int64_t* bytes) try {
   if (!bytes) return GSPMD_ERR_NULL;
   int64_t P = 0;
   const int32_t st = validate_mesh(mesh, &P);
   if (st != GSPMD_OK) return st;
   *bytes = round_up(P * 8, kWsAlign) + round_up(P * static_cast<int64_t>(sizeof(ReshardDesc)), kWsAlign);
   return GSPMD_OK;
-}
+} catch (...) { return GSPMD_ERR_HOST_MEMORY; }
 
 int32_t gspmd_reshard(const gspmd_mesh* mesh, const gspmd_sharding* src_sh, const gspmd_shard_buf* src_shards,
                       const gspmd_sharding* dst_sh, const gspmd_shard_buf* dst_shards,
-                      void* workspace, int64_t workspace_bytes, void* hip_stream) {
+                      void* workspace, int64_t workspace_bytes, void* hip_stream) try {
   if (!src_shards || !dst_shards) return GSPMD_ERR_NULL;
   int64_t P = 0;
   int32_t st = validate_mesh(mesh, &P);
@@ -717,16 +732,26 @@ int32_t gspmd_reshard(const gspmd_mesh* mesh, const gspmd_sharding* src_sh, cons
   }
   if (descs.empty()) return GSPMD_OK;
 
-  // workspace = [src shard of the partition at each mesh position][descriptors]
-  const int64_t ids_bytes = round_up(P * 8, kWsAlign);
-  std::vector<char> host(static_cast<size_t>(ids_bytes + descs.size() * sizeof(ReshardDesc)), 0);
-  for (int64_t pos = 0; pos < P; ++pos) std::memcpy(host.data() + pos * 8, &src_shards[mesh->device_ids[pos]].data, 8);
-  std::memcpy(host.data() + ids_bytes, descs.data(), descs.size() * sizeof(ReshardDesc));
+  // tables: [src shard of the partition at each mesh position][descriptors]; as kernel arguments when they fit,
+  // else uploaded into the workspace (stream-ordered copy from a temporary host buffer)
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  if (hipMemcpyAsync(workspace, host.data(), host.size(), hipMemcpyHostToDevice, stream) != hipSuccess) return GSPMD_ERR_DEVICE;
-  const char* ws = static_cast<const char*>(workspace);
-  const void* const* d_ptrs = reinterpret_cast<const void* const*>(ws);
-  const ReshardDesc* d_descs = reinterpret_cast<const ReshardDesc*>(ws + ids_bytes);
+  InlineReshard inl;
+  std::memset(&inl, 0, sizeof(inl));
+  const void* const* d_ptrs = nullptr;
+  const ReshardDesc* d_descs = nullptr;
+  if (P <= kInlineReshardSrc && descs.size() <= static_cast<size_t>(kInlineReshardDescs)) {
+    for (int64_t pos = 0; pos < P; ++pos) inl.src[pos] = src_shards[mesh->device_ids[pos]].data;
+    std::memcpy(inl.d, descs.data(), descs.size() * sizeof(ReshardDesc));
+  } else {
+    const int64_t ids_bytes = round_up(P * 8, kWsAlign);
+    std::vector<char> host(static_cast<size_t>(ids_bytes + descs.size() * sizeof(ReshardDesc)), 0);
+    for (int64_t pos = 0; pos < P; ++pos) std::memcpy(host.data() + pos * 8, &src_shards[mesh->device_ids[pos]].data, 8);
+    std::memcpy(host.data() + ids_bytes, descs.data(), descs.size() * sizeof(ReshardDesc));
+    if (hipMemcpyAsync(workspace, host.data(), host.size(), hipMemcpyHostToDevice, stream) != hipSuccess) return GSPMD_ERR_DEVICE;
+    const char* ws = static_cast<const char*>(workspace);
+    d_ptrs = reinterpret_cast<const void* const*>(ws);
+    d_descs = reinterpret_cast<const ReshardDesc*>(ws + ids_bytes);
+  }
 
   const int v = vec ? vec_elems : 1;
   const int64_t gx = ((max_cols + v - 1) / v + 255) / 256;
@@ -734,14 +759,14 @@ int32_t gspmd_reshard(const gspmd_mesh* mesh, const gspmd_sharding* src_sh, cons
   const int64_t gy = std::min<int64_t>(std::min<int64_t>(max_rows, 65535), std::max<int64_t>(1, 8192 / (gx * static_cast<int64_t>(descs.size()))));
   const dim3 block(256), grid(static_cast<unsigned>(gx), static_cast<unsigned>(gy), static_cast<unsigned>(descs.size()));
   if (dtype == GSPMD_BF16) {
-    if (vec) hipLaunchKernelGGL((reshard_kernel<bf16_bits, 8>), grid, block, 0, stream, d_descs, d_ptrs);
-    else hipLaunchKernelGGL((reshard_kernel<bf16_bits, 1>), grid, block, 0, stream, d_descs, d_ptrs);
+    if (vec) hipLaunchKernelGGL((reshard_kernel<bf16_bits, 8>), grid, block, 0, stream, inl, d_descs, d_ptrs);
+    else hipLaunchKernelGGL((reshard_kernel<bf16_bits, 1>), grid, block, 0, stream, inl, d_descs, d_ptrs);
   } else {
-    if (vec) hipLaunchKernelGGL((reshard_kernel<uint32_t, 4>), grid, block, 0, stream, d_descs, d_ptrs);
-    else hipLaunchKernelGGL((reshard_kernel<uint32_t, 1>), grid, block, 0, stream, d_descs, d_ptrs);
+    if (vec) hipLaunchKernelGGL((reshard_kernel<uint32_t, 4>), grid, block, 0, stream, inl, d_descs, d_ptrs);
+    else hipLaunchKernelGGL((reshard_kernel<uint32_t, 1>), grid, block, 0, stream, inl, d_descs, d_ptrs);
   }
   return hipGetLastError() == hipSuccess ? GSPMD_OK : GSPMD_ERR_DEVICE;
-}
+} catch (...) { return GSPMD_ERR_HOST_MEMORY; }
 
 namespace {
 
@@ -809,7 +834,7 @@ int64_t layout_temps(const gspmd_mesh* mesh, const gspmd_sharding* sh, int64_t P
 
 int32_t gspmd_compatible_operand_shardings(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
                                            const gspmd_sharding* lhs_sh, const gspmd_sharding* rhs_sh,
-                                           const gspmd_sharding* out_sh, int32_t* lhs_mapping, int32_t* rhs_mapping) {
+                                           const gspmd_sharding* out_sh, int32_t* lhs_mapping, int32_t* rhs_mapping) try {
   if (!lhs_mapping || !rhs_mapping) return GSPMD_ERR_NULL;
   int32_t st = validate_mesh(mesh, nullptr);
   if (st != GSPMD_OK) return st;
@@ -844,11 +869,11 @@ int32_t gspmd_compatible_operand_shardings(const gspmd_mesh* mesh, const gspmd_d
     }
   }
   return GSPMD_OK;
-}
+} catch (...) { return GSPMD_ERR_HOST_MEMORY; }
 
 int32_t gspmd_resharded_dot_workspace_bytes(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
                                             const gspmd_sharding* lhs_sh, const gspmd_sharding* rhs_sh,
-                                            const gspmd_sharding* out_sh, int32_t in_dtype, int64_t* bytes) {
+                                            const gspmd_sharding* out_sh, int32_t in_dtype, int64_t* bytes) try {
   if (!bytes) return GSPMD_ERR_NULL;
   if (!is_dtype(in_dtype)) return GSPMD_ERR_UNSUPPORTED;
   int32_t lmap[kMaxRank], rmap[kMaxRank];
@@ -871,14 +896,14 @@ int32_t gspmd_resharded_dot_workspace_bytes(const gspmd_mesh* mesh, const gspmd_
   if ((st = gspmd_dot_workspace_bytes(mesh, dims, &l2, &r2, out_sh, -1, 1, &n)) != GSPMD_OK) return st;
   *bytes = total + n;
   return GSPMD_OK;
-}
+} catch (...) { return GSPMD_ERR_HOST_MEMORY; }
 
 int32_t gspmd_resharded_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
                             const gspmd_shard_buf* lhs_shards, const gspmd_sharding* lhs_sh,
                             const gspmd_shard_buf* rhs_shards, const gspmd_sharding* rhs_sh,
                             const gspmd_shard_buf* out_shards, const gspmd_sharding* out_sh,
                             const int64_t* lhs_fill, int32_t epilogue,
-                            void* workspace, int64_t workspace_bytes, void* hip_stream) {
+                            void* workspace, int64_t workspace_bytes, void* hip_stream) try {
   if (!lhs_shards || !rhs_shards || !out_shards) return GSPMD_ERR_NULL;
   int32_t lmap[kMaxRank], rmap[kMaxRank];
   int32_t st = gspmd_compatible_operand_shardings(mesh, dims, lhs_sh, rhs_sh, out_sh, lmap, rmap);
@@ -916,6 +941,6 @@ int32_t gspmd_resharded_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
   }
   const int64_t left = workspace_bytes - (ws - static_cast<char*>(workspace));
   return gspmd_grouped_dot(mesh, dims, luse, &l2, ruse, &r2, out_shards, out_sh, lhs_fill, epilogue, ws, left, hip_stream);
-}
+} catch (...) { return GSPMD_ERR_HOST_MEMORY; }
 
 }  // extern "C"

@@ -60,6 +60,47 @@ __device__ __forceinline__ int find_problem(const Problem* __restrict__ tab, int
   return lo;
 }
 
+// Launch tables small enough to travel as kernel arguments (no upload, so such a launch can be recorded into a HIP
+// graph): up to kInlineProblems problems and kInlineRects zero-fill rectangles.  Larger tables are read from device
+// memory (`tab` non-null).
+constexpr int kInlineProblems = 32;
+constexpr int kInlineRects = 2 * kInlineProblems;
+struct InlineProblems { Problem p[kInlineProblems]; };
+struct InlineRects { ZeroRect r[kInlineRects]; };
+
+// The kernel-argument segment, read in place: loads from it with a wave-uniform index are scalar loads.  (A by-value
+// struct parameter that is indexed dynamically through its C++ name is first copied to private memory.)  The table
+// read this way must be the kernel's FIRST parameter, which sits at offset 0 of the segment.
+#define GSPMD_KERNARG __attribute__((address_space(4)))
+template <typename T>
+__device__ __forceinline__ const GSPMD_KERNARG T* first_kernel_argument() {
+  return (const GSPMD_KERNARG T*)__builtin_amdgcn_kernarg_segment_ptr();
+}
+template <typename T>
+__device__ __forceinline__ T copy_from_kernarg(const GSPMD_KERNARG T* p) {
+  static_assert(sizeof(T) % 8 == 0, "copied as 64-bit words");
+  const GSPMD_KERNARG uint64_t* q = (const GSPMD_KERNARG uint64_t*)p;
+  uint64_t w[sizeof(T) / 8];
+#pragma unroll
+  for (size_t i = 0; i < sizeof(T) / 8; ++i) w[i] = q[i];
+  T out;
+  __builtin_memcpy(&out, w, sizeof(T));
+  return out;
+}
+
+// The problem that owns output tile `tile`, from the table in device memory if there is one, else from the table in
+// the kernel arguments (an InlineProblems as first parameter).
+__device__ __forceinline__ Problem lookup_problem(const Problem* __restrict__ tab, int n_prob, int tile) {
+  if (tab) return tab[find_problem(tab, n_prob, tile)];
+  const GSPMD_KERNARG Problem* inl = first_kernel_argument<Problem>();
+  int lo = 0, hi = n_prob - 1;
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (inl[mid].tile_begin <= tile) lo = mid; else hi = mid - 1;
+  }
+  return copy_from_kernarg(inl + lo);
+}
+
 constexpr int kGenTile = 64;   // output tile edge of the fallback kernel
 constexpr int kGenBK = 16;
 
@@ -67,11 +108,11 @@ constexpr int kGenBK = 16;
 // Every load is predicated on the valid extents (masked positions contribute 0 and are never
 // read); stores cover the static extents and write 0 outside the valid region.
 template <typename TIn, typename TOut>
-__global__ __launch_bounds__(256) void dot_fallback_kernel(const Problem* __restrict__ tab, int n_prob, int layout, int epilogue) {
+__global__ __launch_bounds__(256) void dot_fallback_kernel(const InlineProblems inl, const Problem* __restrict__ tab, int n_prob, int layout, int epilogue) {
   __shared__ float As[kGenBK][kGenTile + 4];   // [k][m]
   __shared__ float Bs[kGenBK][kGenTile + 4];   // [k][n]
   const int tile = blockIdx.x;
-  const Problem P = tab[find_problem(tab, n_prob, tile)];
+  const Problem P = lookup_problem(tab, n_prob, tile);
   const int local = tile - P.tile_begin;
   const int m0 = (local / P.tiles_n) * kGenTile, n0 = (local % P.tiles_n) * kGenTile;
   const TIn* __restrict__ A = static_cast<const TIn*>(P.A);
@@ -130,8 +171,8 @@ __global__ __launch_bounds__(256) void dot_fallback_kernel(const Problem* __rest
 // grid.y = rectangle, grid.x strides over its 16-byte vectors (VEC elements; the host picks VEC = 1 unless the
 // pointers, leading dimensions, first columns and widths of all rectangles allow 16-byte stores).
 template <typename TOut, int VEC>
-__global__ __launch_bounds__(256) void zero_rects_kernel(const ZeroRect* __restrict__ rects) {
-  const ZeroRect R = rects[blockIdx.y];
+__global__ __launch_bounds__(256) void zero_rects_kernel(const InlineRects inl, const ZeroRect* __restrict__ rects) {
+  const ZeroRect R = rects ? rects[blockIdx.y] : copy_from_kernarg(first_kernel_argument<ZeroRect>() + blockIdx.y);
   const int wv = (R.c1 - R.c0) / VEC;
   const int64_t total = static_cast<int64_t>(R.r1 - R.r0) * wv;
   TOut* __restrict__ C = static_cast<TOut*>(R.C);
@@ -287,9 +328,9 @@ struct ReshardDesc {              // one per distinct dst buffer
 // 16-byte aligned pointers (checked on the host).  The owner of an element changes only when a row crosses into
 // another src shard, so the src pointer (src_by_pos[mesh position], composed on the host from the device-id tensor) is
 // fetched again only then.
-template <typename T, int VEC>
-__global__ __launch_bounds__(256) void reshard_kernel(const ReshardDesc* __restrict__ descs, const void* const* __restrict__ src_by_pos) {
-  const ReshardDesc& d = descs[blockIdx.z];
+template <typename T, int VEC, typename DescPtr, typename SrcPtr>
+__device__ __forceinline__ void reshard_body(DescPtr dp, SrcPtr src_by_pos) {
+  const auto& d = *dp;
   const int last = d.rank - 1;
   const int c = (blockIdx.x * blockDim.x + threadIdx.x) * VEC;
   if (c >= d.shard[last]) return;
@@ -339,6 +380,25 @@ __global__ __launch_bounds__(256) void reshard_kernel(const ReshardDesc* __restr
     } else {
       *reinterpret_cast<Vec*>(dst + o) = v;
     }
+  }
+}
+
+// Tables small enough to travel as kernel arguments (no upload): up to kInlineReshardSrc partitions and
+// kInlineReshardDescs distinct dst buffers; larger ones are read from device memory (`descs` non-null).
+constexpr int kInlineReshardSrc = 64, kInlineReshardDescs = 8;
+struct InlineReshard {
+  const void* src[kInlineReshardSrc];
+  ReshardDesc d[kInlineReshardDescs];
+};
+
+template <typename T, int VEC>
+__global__ __launch_bounds__(256) void reshard_kernel(const InlineReshard inl, const ReshardDesc* __restrict__ descs,
+                                                      const void* const* __restrict__ src_by_pos) {
+  if (descs) {
+    reshard_body<T, VEC>(descs + blockIdx.z, src_by_pos);
+  } else {
+    const GSPMD_KERNARG InlineReshard* in_args = first_kernel_argument<InlineReshard>();
+    reshard_body<T, VEC>(&in_args->d[blockIdx.z], &in_args->src[0]);
   }
 }
 

@@ -28,6 +28,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "kernels_basic.h"
 #include "mainloop_asm.h"
 #include "plan.h"
@@ -64,7 +66,7 @@ __device__ __forceinline__ u32x4_t mask_tail8(u32x4_t v, int keep) {   // keep f
 }
 
 template <typename TOut, int LAYOUT>
-__global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const Problem* __restrict__ tab, int n_prob, int epilogue) {
+__global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const InlineProblems inl, const Problem* __restrict__ tab, int n_prob, int epilogue) {
   constexpr bool AKM = (LAYOUT & GSPMD_LAYOUT_LHS_K_MAJOR) != 0, BKC = (LAYOUT & GSPMD_LAYOUT_RHS_K_CONTIGUOUS) != 0;
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   const int t = threadIdx.x, lane = t & 63;
@@ -72,7 +74,7 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const Problem* _
   const int wm = wave >> 2, wn = wave & 3;     // wm is also the ping-pong group
 
   const int tile = logical_tile(blockIdx.x, gridDim.x);
-  const Problem P = tab[find_problem(tab, n_prob, tile)];
+  const Problem P = lookup_problem(tab, n_prob, tile);
   int m0, n0;
   tile_origin(tile - P.tile_begin, P.Mv, P.tiles_n, &m0, &n0);
 
@@ -284,7 +286,9 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const Problem* _
   // ---- epilogue: lane holds, for row m, columns n .. n+3 of each 16-column block
   TOut* __restrict__ Cg = static_cast<TOut*>(P.C);
   const bool vec_ok = ((P.ldc & 3) == 0) && ((reinterpret_cast<uintptr_t>(Cg) & 15) == 0);
-  if (vec_ok && m0 + kMfmaBM <= P.Mv && n0 + kMfmaBN <= P.Nv) {
+  // the whole-tile path stores 16 bytes per lane: rows of 8 bf16 or 4 fp32 elements must keep that alignment
+  const bool rows_16b = (P.ldc & (16 / static_cast<int>(sizeof(TOut)) - 1)) == 0;
+  if (vec_ok && rows_16b && m0 + kMfmaBM <= P.Mv && n0 + kMfmaBN <= P.Nv) {
     // tile wholly inside the valid region: no predicates; bf16 through the hardware round-to-nearest-even conversion
     if constexpr (sizeof(TOut) == 2) {
       // bf16: the wave's 128 x 64 block is a 128-byte line per row, but a lane holds only 8 bytes of it per 16-column
@@ -367,27 +371,34 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const Problem* _
   }
 }
 
+constexpr int kMaxDevices = 64;
+
+// The kernel needs all 160 KiB of LDS as dynamic shared memory: raised once per instantiation and device.  Callable
+// from several host threads.
 template <typename TOut, int LAYOUT>
-inline bool launch_dot_mfma_as(const Problem* tab, int n_prob, int tiles, int epilogue, hipStream_t stream) {
-  static bool attr_done = false;
-  if (!attr_done) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&dot_mfma_kernel<TOut, LAYOUT>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, kMfmaLds) != hipSuccess) return false;
-    attr_done = true;
-  }
+inline bool launch_dot_mfma_as(const InlineProblems& inl, const Problem* tab, int n_prob, int tiles, int epilogue, hipStream_t stream) {
+  static std::once_flag once[kMaxDevices];
+  static bool ok[kMaxDevices];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return false;
+  std::call_once(once[dev], [dev] {
+    ok[dev] = hipFuncSetAttribute(reinterpret_cast<const void*>(&dot_mfma_kernel<TOut, LAYOUT>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, kMfmaLds) == hipSuccess;
+  });
+  if (!ok[dev]) return false;
   const dim3 grid(static_cast<unsigned>(tiles)), block(kMfmaThreads);
-  hipLaunchKernelGGL((dot_mfma_kernel<TOut, LAYOUT>), grid, block, kMfmaLds, stream, tab, n_prob, epilogue);
+  hipLaunchKernelGGL((dot_mfma_kernel<TOut, LAYOUT>), grid, block, kMfmaLds, stream, inl, tab, n_prob, epilogue);
   return hipGetLastError() == hipSuccess;
 }
 
-inline bool launch_dot_mfma(const Problem* tab, int n_prob, int tiles, int32_t layout, int32_t out_dtype, int epilogue,
-                            hipStream_t stream) {
+inline bool launch_dot_mfma(const InlineProblems& inl, const Problem* tab, int n_prob, int tiles, int32_t layout, int32_t out_dtype,
+                            int epilogue, hipStream_t stream) {
   const bool f32 = out_dtype == GSPMD_F32;
   switch (layout & 3) {
-    case 0: return f32 ? launch_dot_mfma_as<float, 0>(tab, n_prob, tiles, epilogue, stream) : launch_dot_mfma_as<bf16_bits, 0>(tab, n_prob, tiles, epilogue, stream);
-    case 1: return f32 ? launch_dot_mfma_as<float, 1>(tab, n_prob, tiles, epilogue, stream) : launch_dot_mfma_as<bf16_bits, 1>(tab, n_prob, tiles, epilogue, stream);
-    case 2: return f32 ? launch_dot_mfma_as<float, 2>(tab, n_prob, tiles, epilogue, stream) : launch_dot_mfma_as<bf16_bits, 2>(tab, n_prob, tiles, epilogue, stream);
-    default: return f32 ? launch_dot_mfma_as<float, 3>(tab, n_prob, tiles, epilogue, stream) : launch_dot_mfma_as<bf16_bits, 3>(tab, n_prob, tiles, epilogue, stream);
+    case 0: return f32 ? launch_dot_mfma_as<float, 0>(inl, tab, n_prob, tiles, epilogue, stream) : launch_dot_mfma_as<bf16_bits, 0>(inl, tab, n_prob, tiles, epilogue, stream);
+    case 1: return f32 ? launch_dot_mfma_as<float, 1>(inl, tab, n_prob, tiles, epilogue, stream) : launch_dot_mfma_as<bf16_bits, 1>(inl, tab, n_prob, tiles, epilogue, stream);
+    case 2: return f32 ? launch_dot_mfma_as<float, 2>(inl, tab, n_prob, tiles, epilogue, stream) : launch_dot_mfma_as<bf16_bits, 2>(inl, tab, n_prob, tiles, epilogue, stream);
+    default: return f32 ? launch_dot_mfma_as<float, 3>(inl, tab, n_prob, tiles, epilogue, stream) : launch_dot_mfma_as<bf16_bits, 3>(inl, tab, n_prob, tiles, epilogue, stream);
   }
 }
 

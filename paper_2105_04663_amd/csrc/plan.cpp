@@ -12,7 +12,7 @@ int32_t validate_mesh(const gspmd_mesh* mesh, int64_t* n_partitions) {
   int64_t p = 1;
   for (int i = 0; i < mesh->rank; ++i) {
     if (mesh->shape[i] <= 0) return GSPMD_ERR_BAD_MESH;
-    if (p > (int64_t(1) << 40) / mesh->shape[i]) return GSPMD_ERR_BAD_MESH;
+    if (p > kMaxPartitions / mesh->shape[i]) return GSPMD_ERR_BAD_MESH;   // bounds the host tables built per partition
     p *= mesh->shape[i];
   }
   // ids must be a permutation of 0..P-1 (every partition owns exactly one mesh position)

@@ -42,6 +42,7 @@ constexpr int64_t kTableBytesPerProblem = sizeof(Problem) + 2 * sizeof(ZeroRect)
 
 constexpr int kMaxRank = 8;
 constexpr int64_t kMaxProblems = 1 << 20;
+constexpr int64_t kMaxPartitions = 1 << 20;
 
 struct Bounds {
   int rank = 0;
@@ -65,10 +66,6 @@ struct DotRoles {
 int32_t analyse_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
                     const gspmd_sharding* lhs_sh, const gspmd_sharding* rhs_sh,
                     const gspmd_sharding* out_sh, DotRoles* roles, int32_t* axis_class);
-
-struct OutBlock {          // where a partition's output block lives (dense view)
-  int64_t elems = 0;       // static shard elements
-};
 
 // Append the GEMM problems of partition `pid` to `out` (tile fields left 0).
 // `c_override`/`c_dtype`: when non-null the output goes to a dense fp32 partial buffer
