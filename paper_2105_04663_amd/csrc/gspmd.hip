@@ -85,6 +85,10 @@ int32_t launch_problems(std::vector<Problem>& all, int32_t layout, int32_t in_dt
   }
   const bool inline_tables = ps.size() <= static_cast<size_t>(kInlineProblems) && rects.size() <= static_cast<size_t>(kInlineRects);
   const int64_t prob_bytes = static_cast<int64_t>(ps.size()) * sizeof(Problem);
+  const int64_t table_bytes = prob_bytes + static_cast<int64_t>(rects.size()) * sizeof(ZeroRect);
+  // the workspace contract does not depend on which way the tables travel
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kWsAlign - 1)) || workspace_bytes < table_bytes)
+    return GSPMD_ERR_WORKSPACE;
   const Problem* tab = nullptr;
   const ZeroRect* drects = nullptr;
   InlineProblems inl;
@@ -95,9 +99,6 @@ int32_t launch_problems(std::vector<Problem>& all, int32_t layout, int32_t in_dt
     if (!ps.empty()) std::memcpy(inl.p, ps.data(), static_cast<size_t>(prob_bytes));
     if (!rects.empty()) std::memcpy(inl_rects.r, rects.data(), rects.size() * sizeof(ZeroRect));
   } else {
-    const int64_t table_bytes = prob_bytes + static_cast<int64_t>(rects.size()) * sizeof(ZeroRect);
-    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kWsAlign - 1)) || workspace_bytes < table_bytes)
-      return GSPMD_ERR_WORKSPACE;
     std::vector<char> host(static_cast<size_t>(table_bytes));
     if (prob_bytes) std::memcpy(host.data(), ps.data(), static_cast<size_t>(prob_bytes));
     if (!rects.empty()) std::memcpy(host.data() + prob_bytes, rects.data(), rects.size() * sizeof(ZeroRect));
