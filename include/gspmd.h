@@ -238,6 +238,21 @@ int32_t gspmd_grouped_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
                           const int64_t* lhs_fill, int32_t epilogue,
                           void* workspace, int64_t workspace_bytes, void* hip_stream);
 
+/* gspmd_grouped_dot for callers that cannot allocate device memory and so cannot provide a workspace (code under
+ * HIP-graph capture, tight serving loops, harnesses that forbid hipMalloc): the same computation, with the launch
+ * tables and the fp32 partials of a contracting split kept in a static device array of
+ * GSPMD_NOALLOC_MAX_WORKSPACE_BYTES that the library holds on every GPU it is loaded on until the process ends.  Calls
+ * nothing that allocates.  GSPMD_ERR_WORKSPACE if gspmd_dot_workspace_bytes(..., partition_id = -1) exceeds that size.
+ * Every call on a GPU uses that GPU's one array (found on the current device at the first call there): calls that
+ * overlap in time on one GPU -- different streams, different host threads -- race; the array keeps the last call's
+ * contents, nothing in it needs to start out as zero.  Other arguments and results as gspmd_grouped_dot. */
+#define GSPMD_NOALLOC_MAX_WORKSPACE_BYTES (32 * 1024 * 1024)
+int32_t gspmd_grouped_dot_noalloc(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
+                                  const gspmd_shard_buf* lhs_shards, const gspmd_sharding* lhs_sh,
+                                  const gspmd_shard_buf* rhs_shards, const gspmd_sharding* rhs_sh,
+                                  const gspmd_shard_buf* out_shards, const gspmd_sharding* out_sh,
+                                  const int64_t* lhs_fill, int32_t epilogue, void* hip_stream);
+
 /* out[i] = partials[0][i] + partials[1][i] + ... + partials[n_partials-1][i] in fp32, in that
  * order (the arithmetic of the AllReduce/ReduceScatter of Section 4.2 along a contracting
  * mesh dimension).  partials: host array of n_partials (1..16) device pointers to dense fp32

@@ -16,7 +16,9 @@ EXPORTED_SYMBOLS = (
     "gspmd_local_dot", "gspmd_grouped_dot", "gspmd_reduce_partials", "gspmd_shard_extract",
     "gspmd_shard_assemble", "gspmd_plan_dot", "gspmd_infer_out_sharding", "gspmd_reshard_workspace_bytes", "gspmd_reshard",
     "gspmd_compatible_operand_shardings", "gspmd_resharded_dot_workspace_bytes", "gspmd_resharded_dot",
+    "gspmd_grouped_dot_noalloc",
 )
+NOALLOC_MAX_WORKSPACE_BYTES = 32 * 1024 * 1024
 
 
 class GspmdError(RuntimeError):
@@ -74,6 +76,7 @@ def load_library():
     lib.gspmd_dot_workspace_bytes.argtypes = [pm, pd, ps, ps, ps, C.c_int64, C.c_int32, pi64]
     lib.gspmd_local_dot.argtypes = [pm, pd, pb, ps, pb, ps, pb, ps, C.c_int64, pi64, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p]
     lib.gspmd_grouped_dot.argtypes = [pm, pd, pb, ps, pb, ps, pb, ps, pi64, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p]
+    lib.gspmd_grouped_dot_noalloc.argtypes = [pm, pd, pb, ps, pb, ps, pb, ps, pi64, C.c_int32, C.c_void_p]
     lib.gspmd_reduce_partials.argtypes = [C.POINTER(C.c_void_p), C.c_int32, C.c_int64, C.c_void_p, C.c_int32, C.c_void_p]
     lib.gspmd_shard_extract.argtypes = [pm, ps, C.c_int64, C.c_void_p, pb, C.c_uint32, C.c_void_p]
     lib.gspmd_shard_assemble.argtypes = [pm, ps, C.c_int64, pb, C.c_void_p, C.c_void_p]
@@ -259,6 +262,19 @@ def grouped_dot(mesh: Mesh, dims: DotDims, lhs_shards: Sequence[ShardBuf], lhs_s
     _check(load_library().gspmd_grouped_dot(C.byref(m), C.byref(d), _bufs(lhs_shards), C.byref(a), _bufs(rhs_shards), C.byref(b),
                                             _bufs(out_shards), C.byref(o), _fill(lhs_fill), int(epilogue),
                                             C.c_void_p(workspace), int(workspace_bytes), C.c_void_p(stream)), "gspmd_grouped_dot")
+
+
+def grouped_dot_noalloc(mesh: Mesh, dims: DotDims, lhs_shards: Sequence[ShardBuf], lhs_sh: Sharding,
+                        rhs_shards: Sequence[ShardBuf], rhs_sh: Sharding, out_shards: Sequence[ShardBuf], out_sh: Sharding,
+                        lhs_fill=None, stream: int = 0, epilogue: int = EPILOGUE_NONE) -> None:
+    """grouped_dot with the library's static workspace (no workspace argument, nothing allocated)."""
+    P = mesh.n_partitions
+    if not (len(lhs_shards) == len(rhs_shards) == len(out_shards) == P):
+        raise ValueError("one shard buffer per partition is required")
+    m, d, a, b, o = mesh._c(), dims._c(), lhs_sh._c(), rhs_sh._c(), out_sh._c()
+    _check(load_library().gspmd_grouped_dot_noalloc(C.byref(m), C.byref(d), _bufs(lhs_shards), C.byref(a), _bufs(rhs_shards),
+                                                    C.byref(b), _bufs(out_shards), C.byref(o), _fill(lhs_fill), int(epilogue),
+                                                    C.c_void_p(stream)), "gspmd_grouped_dot_noalloc")
 
 
 def reshard_workspace_bytes(mesh: Mesh) -> int:

@@ -17,6 +17,23 @@ namespace {
 
 constexpr int64_t kWsAlign = 256;
 
+// Workspace of gspmd_grouped_dot_noalloc: one copy per GPU the library is loaded on, held until the process ends.  In
+// host code the array's name is only a handle: its device address is looked up once per device (scratch_address).
+constexpr int64_t kScratchBytes = GSPMD_NOALLOC_MAX_WORKSPACE_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+void* scratch_address() {
+  static std::once_flag once[kMaxDevices];
+  static void* addr[kMaxDevices];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::call_once(once[dev], [dev] {
+    void* p = nullptr;
+    addr[dev] = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) == hipSuccess ? p : nullptr;
+  });
+  return addr[dev];
+}
+
 bool is_dtype(int32_t d) { return d == GSPMD_F32 || d == GSPMD_BF16; }
 
 // A tensor with a zero-size dimension has no elements; its buffers may be null pointers.
@@ -552,6 +569,21 @@ int32_t gspmd_grouped_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
     }
   }
   return GSPMD_OK;
+} catch (...) { return GSPMD_ERR_HOST_MEMORY; }
+
+int32_t gspmd_grouped_dot_noalloc(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
+                                  const gspmd_shard_buf* lhs_shards, const gspmd_sharding* lhs_sh,
+                                  const gspmd_shard_buf* rhs_shards, const gspmd_sharding* rhs_sh,
+                                  const gspmd_shard_buf* out_shards, const gspmd_sharding* out_sh,
+                                  const int64_t* lhs_fill, int32_t epilogue, void* hip_stream) try {
+  int64_t need = 0;
+  const int32_t st = gspmd_dot_workspace_bytes(mesh, dims, lhs_sh, rhs_sh, out_sh, -1, lhs_fill != nullptr, &need);
+  if (st != GSPMD_OK) return st;
+  if (need > kScratchBytes) return GSPMD_ERR_WORKSPACE;     // launch tables + fp32 partials do not fit the static array
+  void* ws = scratch_address();
+  if (!ws) return GSPMD_ERR_DEVICE;
+  return gspmd_grouped_dot(mesh, dims, lhs_shards, lhs_sh, rhs_shards, rhs_sh, out_shards, out_sh, lhs_fill, epilogue,
+                           ws, kScratchBytes, hip_stream);
 } catch (...) { return GSPMD_ERR_HOST_MEMORY; }
 
 int32_t gspmd_reduce_partials(const void* const* partials, int32_t n_partials, int64_t n_elems,
