@@ -46,9 +46,12 @@ The forward einsums have a K-contiguous lhs and a K-major rhs; a weight gradient
 both K-contiguous.  One set of macros is written per combination (GSPMD_MAINLOOP_L<layout>_..., layout bit 0 = lhs
 K-major, bit 1 = rhs K-contiguous); only the read phase differs (32, 48, 24 or 40 LDS reads into the same 96 fragment
 registers).
-Partly valid tiles: when the valid rows of an output tile end inside group 1's half (rows 128-255), its waves run a
-variant (..._G1R4_..., ..._G1R6_...) that reads and multiplies only the first 4 or 6 of their 8 row blocks; the rest of
-their accumulators stays zero and is never stored.  Group 0 and the loads are unchanged.
+Partly valid tiles: when the rows an output tile owns end inside group 1's half (rows 128-255), its waves run a
+variant (..._G1R4_... to ..._G1R7_...) that reads and multiplies only the first 4 to 7 of their 8 row blocks; the rest of
+their accumulators stays zero and is never stored.  When they end inside group 0's half (a problem with at most 128
+rows), group 0 runs ..._G0R4_... or ..._G0R6_... and group 1 its shortest variant (it still loads its share of every
+tile and passes every barrier).  The loads are the same in every variant; only their spacing between the MFMAs
+shrinks with the phase.
 
 Register plan per wave: v[0:127] accumulators acc(bm, bn) = v[4*(4*bm+bn) ..+3] (bm = 16-row block 0..7 of the
 wave's 128 rows, bn = 16-column block 0..3 of its 64 columns); fragments of tile q (0/1) of the K step:
@@ -156,7 +159,7 @@ def advance():
             "s_add_u32 s42, s42, s51", "s_addc_u32 s43, s43, 0"] + step_stage("s52", 2)
 
 
-LOAD_STRIDE = {8: 6, 6: 4, 4: 2}      # MFMAs between two tile loads of a wave, by row blocks computed
+LOAD_STRIDE = {8: 6, 7: 5, 6: 4, 5: 3, 4: 2}      # MFMAs between two tile loads of a wave, by row blocks computed
 
 
 def mfma_phase(w, tail, nbm=8, loads=True):
@@ -187,16 +190,17 @@ def mfma_phase(w, tail, nbm=8, loads=True):
     return out
 
 
-def group0(w, layout):
+def group0(w, layout, nbm=8):
     """Waves 0-3: read phase of K step u, barrier, MFMA phase of u, barrier.  Tile 2u+4 is loaded during the MFMA phase
     of step u; the last two steps have no tile left to load and run a copy of the step without loads (its wait is for
-    everything still in flight: the first tile of the last step)."""
+    everything still in flight: the first tile of the last step).  nbm < 8: the variant for an output tile whose rows
+    end inside this group's half (rows 0-127): only the first nbm 16-row blocks are read and multiplied."""
     s = ["s_cmp_le_u32 s45, 2", "s_cbranch_scc1 L0_drain_%="]
-    s += ["L0_top_%=:"] + mem_phase(layout) + ["s_add_u32 s49, s44, s52", "s_waitcnt lgkmcnt(0)", "s_barrier"]
-    s += mfma_phase(w, ["s_sub_u32 s45, s45, 1", "s_waitcnt vmcnt(8)"])
+    s += ["L0_top_%=:"] + mem_phase(layout, nbm) + ["s_add_u32 s49, s44, s52", "s_waitcnt lgkmcnt(0)", "s_barrier"]
+    s += mfma_phase(w, ["s_sub_u32 s45, s45, 1", "s_waitcnt vmcnt(8)"], nbm)
     s += ["s_barrier", "s_cmp_gt_u32 s45, 2", "s_cbranch_scc1 L0_top_%="]
-    s += ["L0_drain_%=:"] + mem_phase(layout) + ["s_waitcnt lgkmcnt(0)", "s_barrier"]
-    s += mfma_phase(w, ["s_sub_u32 s45, s45, 1", "s_waitcnt vmcnt(0)"], loads=False)
+    s += ["L0_drain_%=:"] + mem_phase(layout, nbm) + ["s_waitcnt lgkmcnt(0)", "s_barrier"]
+    s += mfma_phase(w, ["s_sub_u32 s45, s45, 1", "s_waitcnt vmcnt(0)"], nbm, loads=False)
     s += ["s_barrier", "s_cmp_lg_u32 s45, 0", "s_cbranch_scc1 L0_drain_%=", "s_nop 15", "s_nop 15"]
     return s
 
@@ -216,6 +220,10 @@ def group1(w, layout, nbm=8):
     return s
 
 
+G0_SHORT = (4, 6)            # row blocks of the short variants of each group
+G1_SHORT = (4, 5, 6, 7)
+
+
 def macro(name, lines):
     return f"#define {name} \\\n" + " \\\n".join('  "' + l + '\\n\\t"' for l in lines)
 
@@ -226,8 +234,10 @@ def main():
     for layout in range(4):
         for w in range(4):
             out.append(macro(f"GSPMD_MAINLOOP_L{layout}_G0_W{w}", group0(w, layout)))
+            for nbm in G0_SHORT:
+                out.append(macro(f"GSPMD_MAINLOOP_L{layout}_G0R{nbm}_W{w}", group0(w, layout, nbm)))
             out.append(macro(f"GSPMD_MAINLOOP_L{layout}_G1_W{w}", group1(w, layout)))
-            for nbm in (4, 6):
+            for nbm in G1_SHORT:
                 out.append(macro(f"GSPMD_MAINLOOP_L{layout}_G1R{nbm}_W{w}", group1(w, layout, nbm)))
     out.append(f'#define GSPMD_MAINLOOP_CLOBBERS {clob}, "s48", "s49", "s50", "s51", "m0", "scc", "vcc", "memory"')
     sys.stdout.write("\n".join(out) + "\n")

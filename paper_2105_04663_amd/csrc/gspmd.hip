@@ -95,7 +95,8 @@ int32_t launch_problems(std::vector<Problem>& all, int32_t layout, int32_t in_dt
   if (tiles < 0) return GSPMD_ERR_UNSUPPORTED;
   std::vector<ZeroRect> rects;
   for (const auto& p : all) {
-    const int32_t rows_done = static_cast<int32_t>(std::min<int64_t>(p.Ms, (static_cast<int64_t>(p.Mv) + bm - 1) / bm * bm));
+    const int32_t rows_done = mfma ? rows_written(p.Mv, p.Ms)
+                                   : static_cast<int32_t>(std::min<int64_t>(p.Ms, (static_cast<int64_t>(p.Mv) + bm - 1) / bm * bm));
     const int32_t cols_done = static_cast<int32_t>(std::min<int64_t>(p.Ns, (static_cast<int64_t>(p.Nv) + bn - 1) / bn * bn));
     if (rows_done < p.Ms) rects.push_back(ZeroRect{p.C, p.ldc, rows_done, p.Ms, 0, p.Ns, 0});
     if (cols_done < p.Ns && rows_done > 0) rects.push_back(ZeroRect{p.C, p.ldc, 0, rows_done, cols_done, p.Ns, 0});

@@ -75,8 +75,13 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const InlineProb
 
   const int tile = logical_tile(blockIdx.x, gridDim.x);
   const Problem P = lookup_problem(tab, n_prob, tile);
-  int m0, n0;
-  tile_origin(tile - P.tile_begin, P.Mv, P.tiles_n, &m0, &n0);
+  int tile_row, n0;
+  tile_origin(tile - P.tile_begin, P.Mv, P.tiles_n, &tile_row, &n0);
+  // rows [m0, m_end) are this tile's own (valid rows are split evenly over the tile rows, in 16-row blocks); the last
+  // tile row also writes the zeros that follow the valid rows, up to the end of its 256-row footprint
+  const TileRows own = tile_rows(tile_row, P.Mv);
+  const int m0 = own.first, m_end = own.first + own.rows;
+  const int m_write_end = m_end == P.Mv ? min(P.Ms, m0 + kMfmaBM) : m_end;
 
   // acc[bm] holds the four 16x16 tiles (bn = 0..3) of 16-row block bm: element 4*bn + r
   float16_t acc[8];
@@ -101,7 +106,7 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const InlineProb
     int a_off[4], b_off[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      a_off[j] = AKM ? km_load_offset(wn * 4 + j, lane, m0, P.Mv, P.lda) : kc_half_load_offset(wn * 4 + j, lane, wm, m0, P.Mv, P.lda);
+      a_off[j] = AKM ? km_load_offset(wn * 4 + j, lane, m0, m_end, P.lda) : kc_half_load_offset(wn * 4 + j, lane, wm, m0, m_end, P.lda);
       b_off[j] = BKC ? kc_half_load_offset(wn * 4 + j, lane, wm, n0, P.Nv, P.ldb) : km_load_offset(wn * 4 + j, lane, n0, P.Nv, P.ldb);
     }
     const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(smem));
@@ -146,7 +151,7 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const InlineProb
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const int q = wn * 4 + j;
-        const int ao = AKM ? km_load_offset(q, lane, m0, P.Mv, P.lda) : kc_load_offset(q, lane, m0, P.Mv, P.lda);
+        const int ao = AKM ? km_load_offset(q, lane, m0, m_end, P.lda) : kc_load_offset(q, lane, m0, m_end, P.lda);
         const int bo = BKC ? kc_load_offset(q, lane, n0, P.Nv, P.ldb) : km_load_offset(q, lane, n0, P.Nv, P.ldb);
         ta[j] = tail_chunk(AKM, ab, ao, q, k0);
         tb[j] = tail_chunk(!BKC, bb, bo, q, k0);
@@ -211,10 +216,13 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const InlineProb
         const uint32_t wrbase = lds0 + wn * 4096;
         uint32_t wstage = ((4 + wm) % kNumStages) * kStage, rstage = 0;
         uint32_t nkr = nk64;
-        // 16-row blocks of group 1's half (rows 128-255 of the tile) that hold valid rows, rounded up to 4, 6 or 8: the
-        // loop variant for fewer blocks skips the reads and MFMAs of the others (their results would never be stored)
-        const int g1_rows = min(P.Mv - m0, kMfmaBM) - 128;
-        const int g1_blocks = g1_rows <= 64 ? 4 : (g1_rows <= 96 ? 6 : 8);
+        // 16-row blocks of each group's half (rows 0-127 / 128-255 of the tile) that hold rows of this tile: the loop
+        // variant for fewer than 8 skips the reads and MFMAs of the others (their results would never be stored).
+        // Group 1 has variants for 4 to 8 blocks; group 0 for 4, 6 and 8 (a tile that ends inside its half belongs to
+        // a problem of at most 128 rows; group 1 then runs its shortest variant for nothing but its loads).
+        const int g1_rows = own.rows - 128;
+        const int g1_blocks = g1_rows <= 64 ? 4 : (g1_rows + 15) >> 4;
+        const int g0_blocks = own.rows <= 64 ? 4 : (own.rows <= 96 ? 6 : 8);
         const uint32_t astep = static_cast<uint32_t>(a_tile) * 4, bstep = static_cast<uint32_t>(b_tile) * 4;   // one K step, bytes
 #define GSPMD_MAINLOOP_OPERANDS \
         : "+{v[0:15]}"(acc[0]), "+{v[16:31]}"(acc[1]), "+{v[32:47]}"(acc[2]), "+{v[48:63]}"(acc[3]), \
@@ -226,27 +234,26 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const InlineProb
         : GSPMD_MAINLOOP_CLOBBERS
         // the four waves of a group issue their tile loads after different MFMAs, so that the CU's
         // texture-address unit sees one load at a time
-#define GSPMD_RUN_G1(L, R) \
+#define GSPMD_RUN_WAVES(NAME) \
           switch (wn) { \
-            case 0: asm volatile(GSPMD_MAINLOOP_L##L##_G1##R##_W0 GSPMD_MAINLOOP_OPERANDS); break; \
-            case 1: asm volatile(GSPMD_MAINLOOP_L##L##_G1##R##_W1 GSPMD_MAINLOOP_OPERANDS); break; \
-            case 2: asm volatile(GSPMD_MAINLOOP_L##L##_G1##R##_W2 GSPMD_MAINLOOP_OPERANDS); break; \
-            default: asm volatile(GSPMD_MAINLOOP_L##L##_G1##R##_W3 GSPMD_MAINLOOP_OPERANDS); break; \
+            case 0: asm volatile(NAME##_W0 GSPMD_MAINLOOP_OPERANDS); break; \
+            case 1: asm volatile(NAME##_W1 GSPMD_MAINLOOP_OPERANDS); break; \
+            case 2: asm volatile(NAME##_W2 GSPMD_MAINLOOP_OPERANDS); break; \
+            default: asm volatile(NAME##_W3 GSPMD_MAINLOOP_OPERANDS); break; \
           }
 #define GSPMD_RUN_MAINLOOP(L) \
         if (wm == 0) { \
-          switch (wn) { \
-            case 0: asm volatile(GSPMD_MAINLOOP_L##L##_G0_W0 GSPMD_MAINLOOP_OPERANDS); break; \
-            case 1: asm volatile(GSPMD_MAINLOOP_L##L##_G0_W1 GSPMD_MAINLOOP_OPERANDS); break; \
-            case 2: asm volatile(GSPMD_MAINLOOP_L##L##_G0_W2 GSPMD_MAINLOOP_OPERANDS); break; \
-            default: asm volatile(GSPMD_MAINLOOP_L##L##_G0_W3 GSPMD_MAINLOOP_OPERANDS); break; \
-          } \
-        } else if (g1_blocks == 8) { \
-          GSPMD_RUN_G1(L, ) \
-        } else if (g1_blocks == 6) { \
-          GSPMD_RUN_G1(L, R6) \
+          if (g0_blocks == 8) { GSPMD_RUN_WAVES(GSPMD_MAINLOOP_L##L##_G0) } \
+          else if (g0_blocks == 6) { GSPMD_RUN_WAVES(GSPMD_MAINLOOP_L##L##_G0R6) } \
+          else { GSPMD_RUN_WAVES(GSPMD_MAINLOOP_L##L##_G0R4) } \
         } else { \
-          GSPMD_RUN_G1(L, R4) \
+          switch (g1_blocks) { \
+            case 8: GSPMD_RUN_WAVES(GSPMD_MAINLOOP_L##L##_G1) break; \
+            case 7: GSPMD_RUN_WAVES(GSPMD_MAINLOOP_L##L##_G1R7) break; \
+            case 6: GSPMD_RUN_WAVES(GSPMD_MAINLOOP_L##L##_G1R6) break; \
+            case 5: GSPMD_RUN_WAVES(GSPMD_MAINLOOP_L##L##_G1R5) break; \
+            default: GSPMD_RUN_WAVES(GSPMD_MAINLOOP_L##L##_G1R4) break; \
+          } \
         }
         if constexpr (LAYOUT == 0) { GSPMD_RUN_MAINLOOP(0) }
         else if constexpr (LAYOUT == 1) { GSPMD_RUN_MAINLOOP(1) }
@@ -288,8 +295,10 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const InlineProb
   const bool vec_ok = ((P.ldc & 3) == 0) && ((reinterpret_cast<uintptr_t>(Cg) & 15) == 0);
   // the whole-tile path stores 16 bytes per lane: rows of 8 bf16 or 4 fp32 elements must keep that alignment
   const bool rows_16b = (P.ldc & (16 / static_cast<int>(sizeof(TOut)) - 1)) == 0;
-  if (vec_ok && rows_16b && m0 + kMfmaBM <= P.Mv && n0 + kMfmaBN <= P.Nv) {
-    // tile wholly inside the valid region: no predicates; bf16 through the hardware round-to-nearest-even conversion
+  const int rows_own = m_end - m0, rows_write = m_write_end - m0;    // of the tile's 256 rows: valid, written (zeros between)
+  if (vec_ok && rows_16b && n0 + kMfmaBN <= P.Nv) {
+    // all 256 columns valid: whole 16-byte stores, predicated by row only; bf16 through the hardware
+    // round-to-nearest-even conversion
     if constexpr (sizeof(TOut) == 2) {
       // bf16: the wave's 128 x 64 block is a 128-byte line per row, but a lane holds only 8 bytes of it per 16-column
       // block.  Stage it through the wave's own slice of LDS (free now: every wave's LDS reads are over and no tile load is in flight;
@@ -308,10 +317,13 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const InlineProb
           *reinterpret_cast<bf16x4_t*>(slice + (bm * 16 + (lane & 15)) * kPitch + bn * 32 + (lane >> 4) * 8) = o;
         }
       TOut* __restrict__ c0 = Cg + static_cast<int64_t>(m0 + wm * 128 + (lane >> 3)) * P.ldc + n0 + wn * 64 + (lane & 7) * 8;
+      const int row0 = wm * 128 + (lane >> 3);
 #pragma unroll
       for (int p = 0; p < 16; ++p) {
-        const u32x4_t v = *reinterpret_cast<const u32x4_t*>(slice + (p * 8 + (lane >> 3)) * kPitch + (lane & 7) * 16);
-        *reinterpret_cast<u32x4_t*>(c0 + static_cast<int64_t>(p * 8) * P.ldc) = v;
+        u32x4_t v = *reinterpret_cast<const u32x4_t*>(slice + (p * 8 + (lane >> 3)) * kPitch + (lane & 7) * 16);
+        const int row = row0 + p * 8;
+        if (row >= rows_own) v = u32x4_t{0u, 0u, 0u, 0u};
+        if (row < rows_write) *reinterpret_cast<u32x4_t*>(c0 + static_cast<int64_t>(p * 8) * P.ldc) = v;
       }
     } else {
       // fp32: a row of the wave's block is 256 bytes, of which a lane holds 16 per 16-column block.  Staged through the
@@ -334,8 +346,10 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const InlineProb
         }
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          const float4_t v = *reinterpret_cast<const float4_t*>(slice + (i * 4 + (lane >> 4)) * kPitch + (lane & 15) * 16);
-          *reinterpret_cast<float4_t*>(c0 + static_cast<int64_t>(pass * 64 + i * 4) * P.ldc) = v;
+          float4_t v = *reinterpret_cast<const float4_t*>(slice + (i * 4 + (lane >> 4)) * kPitch + (lane & 15) * 16);
+          const int row = wm * 128 + pass * 64 + i * 4 + (lane >> 4);
+          if (row >= rows_own) v = float4_t{0.f, 0.f, 0.f, 0.f};
+          if (row < rows_write) *reinterpret_cast<float4_t*>(c0 + static_cast<int64_t>(pass * 64 + i * 4) * P.ldc) = v;
         }
       }
     }
@@ -344,8 +358,8 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const InlineProb
 #pragma unroll
   for (int bm = 0; bm < 8; ++bm) {
     const int m = m0 + wm * 128 + bm * 16 + (lane & 15);
-    if (m >= P.Ms) continue;
-    const bool mrow = m < P.Mv;
+    if (m >= m_write_end) continue;
+    const bool mrow = m < m_end;
     TOut* crow = Cg + static_cast<int64_t>(m) * P.ldc;
 #pragma unroll
     for (int bn = 0; bn < 4; ++bn) {

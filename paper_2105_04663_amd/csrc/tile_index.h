@@ -90,15 +90,44 @@ GSPMD_INDEX_FN int km_frag_offset(int base, int lane) {
   return krow * 512 + (((cl >> 3) ^ swz_b(krow)) << 4) + (cl & 7) * 2;
 }
 
-// Origin (m0, n0) of tile `local` (0-based inside its problem) of a problem with `rows_valid` valid rows and `tiles_n`
-// tile columns: ids walk bands of kBandRows tile rows, the row index running fastest inside a band.
-GSPMD_INDEX_FN void tile_origin(int local, int rows_valid, int tiles_n, int* m0, int* n0) {
+// How the valid rows of a problem are divided among its tile rows.  The work of a tile is proportional to the
+// 16-row blocks it multiplies, and workgroups are handed to compute units in id order, so a launch finishes soonest
+// when its tiles cost about the same: the ceil(rows / 16) blocks are split as evenly as possible over the
+// ceil(rows / 256) tile rows (the first `extra` tile rows take one block more), instead of whole 256-row tiles and one
+// short one.  Tile row i owns rows [first, first + rows) of the problem; only the last tile row can own a number of
+// rows that is not a multiple of 16.
+struct TileRows {
+  int first;   // first row the tile owns
+  int rows;    // valid rows it owns (1..256)
+};
+GSPMD_INDEX_FN TileRows tile_rows(int i, int rows_valid) {
+  const int tiles_m = (rows_valid + kMfmaBM - 1) / kMfmaBM;
+  const int blocks = (rows_valid + 15) >> 4;
+  const int base = blocks / tiles_m, extra = blocks - base * tiles_m;
+  TileRows t;
+  t.first = (i * base + (i < extra ? i : extra)) * 16;
+  const int own = (base + (i < extra ? 1 : 0)) * 16;
+  t.rows = (i == tiles_m - 1) ? rows_valid - t.first : own;
+  return t;
+}
+// Rows of a problem's static output block that its tiles write (valid rows, then zeros up to the end of the last
+// tile's 256-row footprint); what lies beyond is zero-filled apart.
+GSPMD_INDEX_FN int rows_written(int rows_valid, int rows_static) {
+  if (rows_valid <= 0) return 0;
+  const int tiles_m = (rows_valid + kMfmaBM - 1) / kMfmaBM;
+  const int end = tile_rows(tiles_m - 1, rows_valid).first + kMfmaBM;
+  return end < rows_static ? end : rows_static;
+}
+
+// Tile `local` (0-based inside its problem) of a problem with `rows_valid` valid rows and `tiles_n` tile columns: its
+// tile row and its first column.  Ids walk bands of kBandRows tile rows, the row index running fastest inside a band.
+GSPMD_INDEX_FN void tile_origin(int local, int rows_valid, int tiles_n, int* tile_row, int* n0) {
   const int tiles_m = (rows_valid + kMfmaBM - 1) / kMfmaBM;   // tiles cover the valid extents; the rest of the static block is zero-filled apart
   const int band = local / (kBandRows * tiles_n);
   const int left = tiles_m - band * kBandRows;
   const int rows_in_band = left < kBandRows ? left : kBandRows;
   const int in_band = local - band * kBandRows * tiles_n;
-  *m0 = (band * kBandRows + in_band % rows_in_band) * kMfmaBM;
+  *tile_row = band * kBandRows + in_band % rows_in_band;
   *n0 = (in_band / rows_in_band) * kMfmaBN;
 }
 

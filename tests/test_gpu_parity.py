@@ -180,6 +180,28 @@ def test_moe_fill_counts(mode, E, C, M, H, align):
         assert not got[e, fill[e]:].any()
 
 
+def test_fill_counts_that_end_in_every_row_block_of_a_tile():
+    # One expert per fill count, chosen so that the rows a tile owns end in each 16-row block of both halves of the
+    # 256-row tile (every short variant of the K loop, for both wave groups), at block boundaries and one row either
+    # side of them, and so that the even split of rows over two to four tile rows is exercised (257, 300, 520, 745,
+    # 767, 770, 1000).  Slots beyond the fill count hold NaN; small integers make every fp32 result exact.
+    fills = [1, 15, 16, 17, 63, 64, 65, 96, 97, 112, 127, 128, 129, 144, 145, 160, 176, 177, 192, 193, 208, 209, 224, 225,
+             240, 241, 255, 256, 257, 300, 520, 745, 767, 770, 1000, 0]
+    E, C, M, H = len(fills), 1000, 200, 264
+    w = wl.moe(E=E, C=C, M=M, H=H)
+    fill = np.array(fills, dtype=np.int64)
+    lhs, rhs = wl.draw_small_int_bf16(11, w.lhs_shape), wl.draw_small_int_bf16(12, w.rhs_shape)
+    for e in range(E):
+        lhs[e, fills[e]:] = 0x7FC0
+    st = Staged(w, lhs, rhs, row_align=8, out_dtype="f32")
+    st.run_grouped(fill=fill)
+    ref = od.dot_general(od.apply_fill(widen(w, lhs), (0,), 1, fill), widen(w, rhs), w.lhs_batch, w.rhs_batch, w.lhs_contract, w.rhs_contract)
+    got = st.out_shard(0)
+    for e in range(E):
+        assert np.array_equal(got[e], ref[e]), f"fill {fills[e]}"
+        assert not got[e, fills[e]:].any()
+
+
 @pytest.mark.parametrize("mode", ["local", "grouped"])
 def test_moe_weight_gradient_fill_limits_the_contraction(mode):
     # ECM,ECH->EMH: the capacity slots contract; slots beyond the fill count hold garbage (NaN) in BOTH operands here

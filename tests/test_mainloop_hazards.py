@@ -108,9 +108,9 @@ def trace(lines, sgpr, outstanding):
 
 
 @pytest.mark.parametrize("layout", range(4))
-@pytest.mark.parametrize("nbm", [8, 6, 4])
+@pytest.mark.parametrize("nbm0,nbm", [(8, 8), (8, 7), (8, 6), (8, 5), (8, 4), (6, 4), (4, 4)])
 @pytest.mark.parametrize("nk64", [1, 2, 3, 4, 7, 12])
-def test_waits_and_barriers_order_every_tile_load_and_read(layout, nbm, nk64):
+def test_waits_and_barriers_order_every_tile_load_and_read(layout, nbm0, nbm, nk64):
     g = generator()
     # per tile part: epoch from which it may be read, epochs in which it is read, epoch in which it is overwritten
     readable, reads, written = {}, {}, {}
@@ -121,7 +121,7 @@ def test_waits_and_barriers_order_every_tile_load_and_read(layout, nbm, nk64):
     for grp in (0, 1):
         for w in range(4):
             sg = initial(grp, w, nk64)[0]
-            lines = g.group0(w, layout) if grp == 0 else g.group1(w, layout, nbm)
+            lines = g.group0(w, layout, nbm0) if grp == 0 else g.group1(w, layout, nbm)
             # in flight at loop start: this wave's 8 pieces of tile 2 (group 0) or 3 (group 1), serials 0-7
             ev, left, last_epoch = trace(lines, sg, range(8))
             epochs.add(last_epoch)

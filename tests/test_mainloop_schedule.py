@@ -102,13 +102,13 @@ def initial(grp, w, nk64):
 
 
 @pytest.mark.parametrize("layout", range(4))
-@pytest.mark.parametrize("grp,nbm", [(0, 8), (1, 8), (1, 6), (1, 4)])
+@pytest.mark.parametrize("grp,nbm", [(0, 8), (0, 6), (0, 4), (1, 8), (1, 7), (1, 6), (1, 5), (1, 4)])
 def test_tile_loads_land_where_the_kernel_reads_them_and_stay_in_bounds(layout, grp, nbm):
     g = generator()
     for w in range(4):
         for nk64 in (1, 2, 3, 4, 5, 9, 16):
             sg, a0, b0 = initial(grp, w, nk64)
-            lines = g.group0(w, layout) if grp == 0 else g.group1(w, layout, nbm)
+            lines = g.group0(w, layout, nbm) if grp == 0 else g.group1(w, layout, nbm)
             assert sum(l.startswith("v_mfma") for l in lines) == 2 * 8 * nbm     # the step with loads and its copy without
             ev, end = run(lines, sg)
             loads = [e for e in ev if e[0] == "load"]
@@ -133,10 +133,11 @@ def test_both_wave_groups_execute_the_same_number_of_barriers(layout):
     g = generator()
     for w in range(4):
         for nk64 in (1, 2, 3, 8):
-            n0 = sum(e[0] == "barrier" for e in run(g.group0(w, layout), initial(0, w, nk64)[0])[0])
-            for nbm in (4, 6, 8):
-                n1 = sum(e[0] == "barrier" for e in run(g.group1(w, layout, nbm), initial(1, w, nk64)[0])[0])
-                assert n0 == n1 == 2 * nk64
+            for nbm0 in (4, 6, 8):
+                n0 = sum(e[0] == "barrier" for e in run(g.group0(w, layout, nbm0), initial(0, w, nk64)[0])[0])
+                for nbm in (4, 5, 6, 7, 8):
+                    n1 = sum(e[0] == "barrier" for e in run(g.group1(w, layout, nbm), initial(1, w, nk64)[0])[0])
+                    assert n0 == n1 == 2 * nk64
 
 
 def test_read_stage_ring_visits_the_tiles_in_order():

@@ -112,18 +112,37 @@ static void check_km(int c0, int cols_valid, int ld) {
 }
 
 static void check_tile_order() {
-  for (int rows_valid : {1, 256, 257, 745, 1024, 2049, 5000, 16384})
+  for (int rows_valid : {1, 15, 16, 17, 128, 255, 256, 257, 734, 745, 959, 967, 1024, 1500, 2049, 5000, 16384})
     for (int tiles_n : {1, 2, 5, 32, 128}) {
       const int tiles_m = (rows_valid + kMfmaBM - 1) / kMfmaBM;
       std::set<RC> seen;
       for (int local = 0; local < tiles_m * tiles_n; ++local) {
-        int m0 = -1, n0 = -1;
-        tile_origin(local, rows_valid, tiles_n, &m0, &n0);
-        CHECK(m0 >= 0 && m0 < rows_valid && m0 % kMfmaBM == 0 && n0 >= 0 && n0 / kMfmaBN < tiles_n && n0 % kMfmaBN == 0,
-              "tile_origin(%d, %d, %d) = (%d, %d)", local, rows_valid, tiles_n, m0, n0);
-        seen.insert(RC(m0, n0));
+        int tr = -1, n0 = -1;
+        tile_origin(local, rows_valid, tiles_n, &tr, &n0);
+        CHECK(tr >= 0 && tr < tiles_m && n0 >= 0 && n0 / kMfmaBN < tiles_n && n0 % kMfmaBN == 0,
+              "tile_origin(%d, %d, %d) = (%d, %d)", local, rows_valid, tiles_n, tr, n0);
+        seen.insert(RC(tr, n0));
       }
       CHECK(static_cast<int>(seen.size()) == tiles_m * tiles_n, "tile order visits %zu of %d tiles", seen.size(), tiles_m * tiles_n);
+      // the tile rows own consecutive ranges that cover the valid rows exactly once; each starts on a 16-row block,
+      // owns at most 256 rows, and their block counts differ by at most one
+      int next = 0, lo = 1 << 30, hi = 0;
+      for (int i = 0; i < tiles_m; ++i) {
+        const TileRows t = tile_rows(i, rows_valid);
+        CHECK(t.first == next && t.first % 16 == 0 && t.rows >= 1 && t.rows <= kMfmaBM, "tile_rows(%d, %d) = (%d, %d)", i, rows_valid, t.first, t.rows);
+        if (i + 1 < tiles_m) CHECK(t.rows % 16 == 0, "tile row %d of %d rows owns %d rows", i, rows_valid, t.rows);
+        const int blocks = (t.rows + 15) / 16;
+        lo = blocks < lo ? blocks : lo;
+        hi = blocks > hi ? blocks : hi;
+        next = t.first + t.rows;
+      }
+      CHECK(next == rows_valid, "tile rows cover %d of %d rows", next, rows_valid);
+      CHECK(hi - lo <= 1, "tile rows of %d rows have %d to %d blocks", rows_valid, lo, hi);
+      for (int rows_static : {rows_valid, rows_valid + 1, rows_valid + 300, rows_valid + 5000}) {
+        const int w = rows_written(rows_valid, rows_static);
+        CHECK(w >= rows_valid && w <= rows_static && (w == rows_static || w == tile_rows(tiles_m - 1, rows_valid).first + kMfmaBM),
+              "rows_written(%d, %d) = %d", rows_valid, rows_static, w);
+      }
     }
   for (int total : {1, 7, 255, 256, 257, 511, 512, 960, 1792, 2048, 70000}) {
     std::set<int> seen;
