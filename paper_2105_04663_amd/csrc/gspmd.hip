@@ -81,8 +81,25 @@ bool mfma_eligible(const std::vector<Problem>& ps, int32_t in_dtype, int32_t lay
 // placed in order), and cost no workgroup launches.  Tables of up to kInlineProblems problems and kInlineRects
 // rectangles travel as kernel arguments; larger ones are uploaded into the workspace with a stream-ordered copy from
 // a temporary host buffer (HIP stages a pageable source before the call returns).
+// Workspace of a launch with joined problems: one arrival counter and join_count slots of kJoinSlotBytes per joined
+// output tile.
+constexpr int64_t kJoinSlotBytes = static_cast<int64_t>(kMfmaBM) * kMfmaBN * 4;
+struct JoinSpace {
+  uint32_t* counters = nullptr;
+  float* partials = nullptr;
+  int64_t tiles = 0;          // joined output tiles
+};
+
+constexpr int64_t kJoinSlack = int64_t(64) << 20;
+// counters of `tiles` joined output tiles, then `slots` slots
+int64_t joined_bytes(int64_t tiles, int64_t slots) { return round_up(tiles * 4, kWsAlign) + slots * kJoinSlotBytes; }
+
+int64_t tiles_of(const Problem& p, int bm, int bn) {
+  return ((static_cast<int64_t>(p.Mv) + bm - 1) / bm) * ((static_cast<int64_t>(p.Nv) + bn - 1) / bn);
+}
+
 int32_t launch_problems(std::vector<Problem>& all, int32_t layout, int32_t in_dtype, int32_t out_dtype, int32_t epilogue,
-                        void* workspace, int64_t workspace_bytes, hipStream_t stream) {
+                        void* workspace, int64_t workspace_bytes, hipStream_t stream, const JoinSpace* join = nullptr) {
   // problems with an empty static output block write nothing
   all.erase(std::remove_if(all.begin(), all.end(), [](const Problem& p) { return p.Ms == 0 || p.Ns == 0; }), all.end());
   if (all.empty()) return GSPMD_OK;
@@ -90,11 +107,13 @@ int32_t launch_problems(std::vector<Problem>& all, int32_t layout, int32_t in_dt
   std::vector<Problem> ps;
   for (const auto& p : all) if (p.Mv > 0) ps.push_back(p);      // Mv, Nv, Kv are all zero or all positive
   const bool mfma = mfma_eligible(ps, in_dtype, layout);
+  if (join && !mfma) return GSPMD_ERR_UNSUPPORTED;              // the caller checks before it joins problems
   const int bm = mfma ? kMfmaBM : kGenTile, bn = mfma ? kMfmaBN : kGenTile;
   const int64_t tiles = assign_tiles(ps, bm, bn);
   if (tiles < 0) return GSPMD_ERR_UNSUPPORTED;
   std::vector<ZeroRect> rects;
   for (const auto& p : all) {
+    if (p.join_slot > 0) continue;                              // one of the joined problems speaks for their common output
     const int32_t rows_done = mfma ? rows_written(p.Mv, p.Ms)
                                    : static_cast<int32_t>(std::min<int64_t>(p.Ms, (static_cast<int64_t>(p.Mv) + bm - 1) / bm * bm));
     const int32_t cols_done = static_cast<int32_t>(std::min<int64_t>(p.Ns, (static_cast<int64_t>(p.Nv) + bn - 1) / bn * bn));
@@ -128,7 +147,13 @@ int32_t launch_problems(std::vector<Problem>& all, int32_t layout, int32_t in_dt
   const int n = static_cast<int>(ps.size());
   if (tiles > 0) {
     if (mfma) {
-      if (!launch_dot_mfma(inl, tab, n, static_cast<int>(tiles), layout, out_dtype, epilogue, stream)) return GSPMD_ERR_DEVICE;
+      if (join && join->tiles > 0) {
+        const unsigned blocks = static_cast<unsigned>(std::min<int64_t>((join->tiles + 255) / 256, 1024));
+        hipLaunchKernelGGL(zero_words_kernel, dim3(blocks), dim3(256), 0, stream, join->counters, join->tiles);
+        if (hipGetLastError() != hipSuccess) return GSPMD_ERR_DEVICE;
+      }
+      if (!launch_dot_mfma(inl, tab, n, static_cast<int>(tiles), layout, out_dtype, epilogue, join ? join->partials : nullptr,
+                           join ? join->counters : nullptr, stream)) return GSPMD_ERR_DEVICE;
     } else {
       const dim3 grid(static_cast<unsigned>(tiles)), block(256);
       if (in_dtype == GSPMD_F32)
@@ -428,16 +453,24 @@ int32_t gspmd_dot_workspace_bytes(const gspmd_mesh* mesh, const gspmd_dot_dims* 
   int64_t P = 1;
   for (int a = 0; a < mesh->rank; ++a) P *= mesh->shape[a];
   if (pid < -1 || pid >= P) return GSPMD_ERR_PARTITION_RANGE;
-  int64_t n_prob = 0, partial_bytes = 0;
+  int64_t n_prob = 0, partial_bytes = 0, tiles = 0;
   const bool contracting = has_contracting(mesh, cls);
   int32_t pmap[kMaxRank];
   partial_mapping(mesh, cls, out_sh, pmap);
   const gspmd_sharding part_sh{out_sh->rank, out_sh->global_shape, pmap};
   for (int64_t p = (pid < 0 ? 0 : pid); p < (pid < 0 ? P : pid + 1); ++p) {
-    int64_t n, e;
-    if ((st = count_partition(mesh, r, lhs_sh, rhs_sh, &part_sh, p, &n, &e)) != GSPMD_OK) return st;
+    int64_t n, e, t;
+    if ((st = count_partition(mesh, r, lhs_sh, rhs_sh, &part_sh, p, &n, &e, &t, kMfmaBM)) != GSPMD_OK) return st;
     n_prob += n;
+    tiles = std::min<int64_t>(tiles + t, int64_t(1) << 40);
     if (pid < 0 && contracting) partial_bytes += round_up(e * 4, kWsAlign);
+  }
+  // A grouped call with a contracting mesh dimension keeps its partial sums either as one dense fp32 array per
+  // partition or, when the problems can be joined in one launch, as one slot per output tile and partition plus a
+  // counter per tile; the second layout is offered only while it stays within reach of the first.
+  if (pid < 0 && contracting && !has_scatter(mesh, cls)) {
+    const int64_t joined = joined_bytes(tiles, tiles);
+    if (joined <= 2 * partial_bytes + kJoinSlack) partial_bytes = std::max(partial_bytes, joined);
   }
   *bytes = round_up(std::max<int64_t>(n_prob, 1) * kTableBytesPerProblem, kWsAlign) + partial_bytes;
   return GSPMD_OK;
@@ -516,6 +549,92 @@ int32_t gspmd_grouped_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
     }
   }
 
+  // Reduce groups: partitions that differ only along contracting mesh dimensions, in ascending mesh position.
+  std::map<std::vector<int64_t>, std::vector<std::pair<int64_t, int64_t>>> groups;   // key -> (lin pos, pid)
+  if (contracting) {
+    for (int64_t p = 0; p < P; ++p) {
+      int64_t coords[kMaxRank];
+      if ((st = mesh_coords(mesh, p, coords)) != GSPMD_OK) return st;
+      std::vector<int64_t> key;
+      int64_t pos = 0;
+      for (int a = 0; a < mesh->rank; ++a) {
+        if (is_contracting(cls[a])) pos = pos * mesh->shape[a] + coords[a];
+        else key.push_back(coords[a]);
+      }
+      groups[key].emplace_back(pos, p);
+    }
+    for (auto& kv : groups) std::sort(kv.second.begin(), kv.second.end());
+  }
+
+  // One launch for the whole sum (the AllReduce of Section 4.2 folded into the contraction): when every member of a
+  // reduce group writes the same out buffer and lowers to the same output blocks, the members' problems are joined --
+  // every output tile gets one contribution per member, added in ascending mesh position by whichever workgroup
+  // finishes last.  Otherwise (a scattered sum, members with out buffers of their own, operands the MFMA kernel cannot
+  // take, a workspace sized for the dense layout only) the partials go to dense arrays and a second kernel sums them.
+  if (contracting && !has_scatter(mesh, cls) && in_dtype == GSPMD_BF16) {
+    std::vector<Problem> joined;
+    int32_t jlayout = 0;
+    int64_t jtiles = 0, jslots = 0;
+    bool ok = true;
+    for (auto& kv : groups) {
+      const auto& members = kv.second;
+      const gspmd_shard_buf& o0 = out_shards[members[0].second];
+      std::vector<std::vector<Problem>> pm(members.size());
+      for (size_t m = 0; m < members.size() && ok; ++m) {
+        const int64_t p = members[m].second;
+        ok = out_shards[p].data == o0.data && out_shards[p].row_stride == o0.row_stride;
+        if (!ok) break;
+        int64_t e = 0;
+        if ((st = plan_partition(mesh, r, &lhs_shards[p], lhs_sh, &rhs_shards[p], rhs_sh, &out_shards[p], out_sh, p, lhs_fill, nullptr,
+                                 &pm[m], &e, &jlayout)) != GSPMD_OK) return st;
+        for (const auto& q : pm[m])
+          if ((q.Kv && (!q.A || !q.B)) || !q.C) return GSPMD_ERR_NULL;
+        ok = pm[m].size() == pm[0].size();
+      }
+      for (size_t i = 0; ok && i < pm[0].size(); ++i) {
+        std::vector<size_t> live;
+        for (size_t m = 0; m < members.size(); ++m) {
+          const Problem &q = pm[m][i], &q0 = pm[0][i];
+          ok = ok && q.C == q0.C && q.ldc == q0.ldc && q.Ms == q0.Ms && q.Ns == q0.Ns;
+          if (q.Kv > 0) {
+            if (!live.empty()) ok = ok && q.Mv == pm[live[0]][i].Mv && q.Nv == pm[live[0]][i].Nv;
+            live.push_back(m);
+          }
+        }
+        if (!ok || live.size() > static_cast<size_t>(kMaxPartials)) { ok = false; break; }
+        if (live.size() <= 1) {
+          joined.push_back(pm[live.empty() ? 0 : live[0]][i]);       // nothing to add up (a dead problem still has its zero fill)
+          continue;
+        }
+        const int64_t t = tiles_of(pm[live[0]][i], kMfmaBM, kMfmaBN);
+        for (size_t k = 0; k < live.size(); ++k) {
+          Problem q = pm[live[k]][i];
+          q.join_count = static_cast<int32_t>(live.size());
+          q.join_slot = static_cast<int32_t>(k);
+          q.join_first = static_cast<int32_t>(jtiles);
+          joined.push_back(q);
+        }
+        jtiles += t;
+        jslots += t * static_cast<int64_t>(live.size());
+        if (jtiles > INT32_MAX) { ok = false; break; }
+      }
+      if (!ok) break;
+    }
+    if (ok) {
+      std::vector<Problem> live;
+      for (const auto& q : joined) if (q.Mv > 0) live.push_back(q);
+      ok = mfma_eligible(live, in_dtype, jlayout);
+    }
+    const int64_t table_area = partial_base - static_cast<char*>(workspace);
+    if (ok && table_area + joined_bytes(jtiles, jslots) <= workspace_bytes) {
+      JoinSpace js;
+      js.counters = reinterpret_cast<uint32_t*>(partial_base);
+      js.partials = reinterpret_cast<float*>(partial_base + round_up(jtiles * 4, kWsAlign));
+      js.tiles = jtiles;
+      return launch_problems(joined, jlayout, in_dtype, out_dtype, epilogue, workspace, workspace_bytes, stream, &js);
+    }
+  }
+
   std::vector<Problem> ps;
   // Partitions that hold the same operands and write the same buffer (replicas along an
   // unused mesh dimension) need the product only once.
@@ -539,23 +658,9 @@ int32_t gspmd_grouped_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
                        workspace, workspace_bytes, stream);
   if (st != GSPMD_OK || !contracting) return st;
 
-  // Sum the partials of each reduce group (partitions that differ only along contracting
-  // mesh dimensions), ascending in mesh position, into every distinct out buffer of the group.
-  std::map<std::vector<int64_t>, std::vector<std::pair<int64_t, int64_t>>> groups;   // key -> (lin pos, pid)
-  for (int64_t p = 0; p < P; ++p) {
-    int64_t coords[kMaxRank];
-    if ((st = mesh_coords(mesh, p, coords)) != GSPMD_OK) return st;
-    std::vector<int64_t> key;
-    int64_t pos = 0;
-    for (int a = 0; a < mesh->rank; ++a) {
-      if (is_contracting(cls[a])) pos = pos * mesh->shape[a] + coords[a];
-      else key.push_back(coords[a]);
-    }
-    groups[key].emplace_back(pos, p);
-  }
+  // Sum the partials of each reduce group, ascending in mesh position, into every distinct out buffer of the group.
   for (auto& kv : groups) {
     auto& members = kv.second;
-    std::sort(members.begin(), members.end());
     if (members.size() > static_cast<size_t>(kMaxPartials)) return GSPMD_ERR_UNSUPPORTED;
     std::vector<const float*> ptrs;
     for (auto& m : members) ptrs.push_back(partial[static_cast<size_t>(m.second)]);

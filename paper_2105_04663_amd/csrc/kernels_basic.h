@@ -188,6 +188,13 @@ __global__ __launch_bounds__(256) void zero_rects_kernel(const InlineRects inl, 
   }
 }
 
+// Arrival counters of joined output tiles start every launch at zero (a fill kernel rather than a memset node, so
+// that the call can be recorded into a HIP graph).
+__global__ __launch_bounds__(256) void zero_words_kernel(uint32_t* __restrict__ words, int64_t n) {
+  for (int64_t i = blockIdx.x * static_cast<int64_t>(blockDim.x) + threadIdx.x; i < n; i += static_cast<int64_t>(gridDim.x) * blockDim.x)
+    words[i] = 0u;
+}
+
 // ---------------------------------------------------------------------------------------
 // Sum of K-partials (the arithmetic of the AllReduce along a contracting mesh dimension).
 // ---------------------------------------------------------------------------------------

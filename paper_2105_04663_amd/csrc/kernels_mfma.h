@@ -66,7 +66,8 @@ __device__ __forceinline__ u32x4_t mask_tail8(u32x4_t v, int keep) {   // keep f
 }
 
 template <typename TOut, int LAYOUT>
-__global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const InlineProblems inl, const Problem* __restrict__ tab, int n_prob, int epilogue) {
+__global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const InlineProblems inl, const Problem* __restrict__ tab, int n_prob, int epilogue,
+                                                                float* __restrict__ join_partials, uint32_t* __restrict__ join_counters) {
   constexpr bool AKM = (LAYOUT & GSPMD_LAYOUT_LHS_K_MAJOR) != 0, BKC = (LAYOUT & GSPMD_LAYOUT_RHS_K_CONTIGUOUS) != 0;
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   const int t = threadIdx.x, lane = t & 63;
@@ -290,6 +291,67 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const InlineProb
     }
   }
 
+  // ---- joined problems (a contracting dimension split over partitions, Section 4.2, or one K range cut in pieces):
+  // every contribution to an output tile is written to its slot of the workspace as fp32, in the accumulators' own
+  // lane order (each wave-instruction stores 1 KiB of consecutive addresses); the workgroup that arrives last at the
+  // tile's counter adds the slots in ascending order -- a fixed order of fp32 additions, whoever arrives last -- and
+  // goes on to the epilogue with the sum.  No workgroup waits for another.
+  // Compute units of different XCDs do not share an L2, so the slots are written and read with device-scope accesses
+  // (the sc1 cache policy: stores go through to memory, loads do not take a stale line), ordered around the device-
+  // scope counter update by a wait for the stores and the workgroup barriers.  A release fence would do the same for
+  // plain stores, but it writes back the XCD's whole L2 and was measured to cost tens of microseconds per tile; an
+  // acquire fence would drop every operand panel the XCD has cached.
+  if (P.join_count > 1) {
+    constexpr int kDeviceScope = 16;                       // sc1
+    const int S = P.join_count;
+    const int64_t jt = static_cast<int64_t>(P.join_first) + (tile - P.tile_begin);
+    const __amdgpu_buffer_rsrc_t slots = __builtin_amdgcn_make_buffer_rsrc(join_partials + ((jt * S) << 16), 0, S << 18, 0x00020000);
+    const int at = (wave * 2048 + lane) * 16;              // this lane's place inside a slot; quad q at + q KiB
+#pragma unroll
+    for (int bm = 0; bm < 8; ++bm)
+#pragma unroll
+      for (int bn = 0; bn < 4; ++bn) {
+        const float4_t v = {acc[bm][4 * bn], acc[bm][4 * bn + 1], acc[bm][4 * bn + 2], acc[bm][4 * bn + 3]};
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, v), slots, at + (bm * 4 + bn) * 1024, P.join_slot << 18, kDeviceScope);
+      }
+    GSPMD_WAIT_ALL();                                      // this wave's stores have reached memory
+    __syncthreads();                                       // ... and so have the other seven waves'
+    uint32_t* flag = reinterpret_cast<uint32_t*>(smem);
+    if (t == 0) *flag = __hip_atomic_fetch_add(join_counters + jt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    const uint32_t before = *flag;
+    if (before != static_cast<uint32_t>(S - 1)) return;
+    // A quarter of the accumulators (8 quads) at a time, three slots (96 spare registers) in flight together, added
+    // in slot order: two round trips to memory per quarter for up to six contributions.
+#pragma unroll
+    for (int qt = 0; qt < 4; ++qt) {
+      for (int sl0 = 0; sl0 < S; sl0 += 3) {
+        u32x4_t in[3][8];
+#pragma unroll
+        for (int d = 0; d < 3; ++d)
+          if (sl0 + d < S) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+              in[d][i] = __builtin_amdgcn_raw_buffer_load_b128(slots, at + (qt * 8 + i) * 1024, (sl0 + d) << 18, kDeviceScope);
+          }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int d = 0; d < 3; ++d)
+          if (sl0 + d < S) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+              const float4_t v = __builtin_bit_cast(float4_t, in[d][i]);
+              const int bm = qt * 2 + (i >> 2), bn = i & 3;
+#pragma unroll
+              for (int r = 0; r < 4; ++r) acc[bm][4 * bn + r] = (sl0 + d == 0) ? v[r] : acc[bm][4 * bn + r] + v[r];
+            }
+          }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    __syncthreads();     // the flag's word is about to be reused as staging
+  }
+
   // ---- epilogue: lane holds, for row m, columns n .. n+3 of each 16-column block
   TOut* __restrict__ Cg = static_cast<TOut*>(P.C);
   const bool vec_ok = ((P.ldc & 3) == 0) && ((reinterpret_cast<uintptr_t>(Cg) & 15) == 0);
@@ -390,7 +452,8 @@ constexpr int kMaxDevices = 64;
 // The kernel needs all 160 KiB of LDS as dynamic shared memory: raised once per instantiation and device.  Callable
 // from several host threads.
 template <typename TOut, int LAYOUT>
-inline bool launch_dot_mfma_as(const InlineProblems& inl, const Problem* tab, int n_prob, int tiles, int epilogue, hipStream_t stream) {
+inline bool launch_dot_mfma_as(const InlineProblems& inl, const Problem* tab, int n_prob, int tiles, int epilogue, float* join_partials,
+                               uint32_t* join_counters, hipStream_t stream) {
   static std::once_flag once[kMaxDevices];
   static bool ok[kMaxDevices];
   int dev = 0;
@@ -401,18 +464,18 @@ inline bool launch_dot_mfma_as(const InlineProblems& inl, const Problem* tab, in
   });
   if (!ok[dev]) return false;
   const dim3 grid(static_cast<unsigned>(tiles)), block(kMfmaThreads);
-  hipLaunchKernelGGL((dot_mfma_kernel<TOut, LAYOUT>), grid, block, kMfmaLds, stream, inl, tab, n_prob, epilogue);
+  hipLaunchKernelGGL((dot_mfma_kernel<TOut, LAYOUT>), grid, block, kMfmaLds, stream, inl, tab, n_prob, epilogue, join_partials, join_counters);
   return hipGetLastError() == hipSuccess;
 }
 
 inline bool launch_dot_mfma(const InlineProblems& inl, const Problem* tab, int n_prob, int tiles, int32_t layout, int32_t out_dtype,
-                            int epilogue, hipStream_t stream) {
+                            int epilogue, float* join_partials, uint32_t* join_counters, hipStream_t stream) {
   const bool f32 = out_dtype == GSPMD_F32;
   switch (layout & 3) {
-    case 0: return f32 ? launch_dot_mfma_as<float, 0>(inl, tab, n_prob, tiles, epilogue, stream) : launch_dot_mfma_as<bf16_bits, 0>(inl, tab, n_prob, tiles, epilogue, stream);
-    case 1: return f32 ? launch_dot_mfma_as<float, 1>(inl, tab, n_prob, tiles, epilogue, stream) : launch_dot_mfma_as<bf16_bits, 1>(inl, tab, n_prob, tiles, epilogue, stream);
-    case 2: return f32 ? launch_dot_mfma_as<float, 2>(inl, tab, n_prob, tiles, epilogue, stream) : launch_dot_mfma_as<bf16_bits, 2>(inl, tab, n_prob, tiles, epilogue, stream);
-    default: return f32 ? launch_dot_mfma_as<float, 3>(inl, tab, n_prob, tiles, epilogue, stream) : launch_dot_mfma_as<bf16_bits, 3>(inl, tab, n_prob, tiles, epilogue, stream);
+    case 0: return f32 ? launch_dot_mfma_as<float, 0>(inl, tab, n_prob, tiles, epilogue, join_partials, join_counters, stream) : launch_dot_mfma_as<bf16_bits, 0>(inl, tab, n_prob, tiles, epilogue, join_partials, join_counters, stream);
+    case 1: return f32 ? launch_dot_mfma_as<float, 1>(inl, tab, n_prob, tiles, epilogue, join_partials, join_counters, stream) : launch_dot_mfma_as<bf16_bits, 1>(inl, tab, n_prob, tiles, epilogue, join_partials, join_counters, stream);
+    case 2: return f32 ? launch_dot_mfma_as<float, 2>(inl, tab, n_prob, tiles, epilogue, join_partials, join_counters, stream) : launch_dot_mfma_as<bf16_bits, 2>(inl, tab, n_prob, tiles, epilogue, join_partials, join_counters, stream);
+    default: return f32 ? launch_dot_mfma_as<float, 3>(inl, tab, n_prob, tiles, epilogue, join_partials, join_counters, stream) : launch_dot_mfma_as<bf16_bits, 3>(inl, tab, n_prob, tiles, epilogue, join_partials, join_counters, stream);
   }
 }
 

@@ -379,7 +379,7 @@ int32_t plan_partition(const gspmd_mesh* mesh, const DotRoles& r,
 int32_t count_partition(const gspmd_mesh* mesh, const DotRoles& r,
                         const gspmd_sharding* lhs_sh, const gspmd_sharding* rhs_sh,
                         const gspmd_sharding* out_sh, int64_t pid,
-                        int64_t* n_problems, int64_t* out_static_elems) {
+                        int64_t* n_problems, int64_t* out_static_elems, int64_t* max_tiles, int tile) {
   // Upper bound that does not depend on the buffers: every batch entry and every index of
   // the free dims except the innermost one of each side may become a problem of its own.
   Bounds lb, rb, ob;
@@ -400,6 +400,11 @@ int32_t count_partition(const gspmd_mesh* mesh, const DotRoles& r,
   for (int i = 0; i < ob.rank; ++i) e *= ob.shard[i];
   *n_problems = n;
   *out_static_elems = e;
+  if (max_tiles) {
+    const int64_t im = r.nlf ? lb.shard[r.lhs_free[r.nlf - 1]] : 1, in = r.nrf ? rb.shard[r.rhs_free[r.nrf - 1]] : 1;
+    const int64_t tm = (im + tile - 1) / tile, tn = (in + tile - 1) / tile, cap = int64_t(1) << 40;
+    *max_tiles = (tm > cap / std::max<int64_t>(tn, 1) || n > cap / std::max<int64_t>(tm * tn, 1)) ? cap : n * tm * tn;
+  }
   return GSPMD_OK;
 }
 

@@ -12,9 +12,12 @@ namespace gspmd {
 
 // One strided GEMM the device kernels run:  C[m,n] = sum_k A[m,k] * B[k,n]  for
 // m < Mv, n < Nv, k < Kv; C is written as 0 for the rest of [Ms, Ns].
-// 64 bytes; the device reads an array of these.  Which index of A and of B is the contiguous
+// 80 bytes; the device reads an array of these.  Which index of A and of B is the contiguous
 // one is the same for every problem of a launch (it follows from the Dot's dimension order)
 // and travels beside the table as a mask of GSPMD_LAYOUT_* bits.
+// Joined problems: join_count > 1 problems of one launch that have the same output block (C, extents) and differ in
+// what they contract over -- the partitions along a contracting mesh dimension (Section 4.2), or pieces of one K
+// range -- each contribute a partial sum to every output tile; the contributions are added in ascending join_slot.
 struct Problem {
   const void* A;      // element (m,k) at A + m*lda + k;  lhs K-major: A + k*lda + m
   const void* B;      // element (k,n) at B + k*ldb + n;  rhs K-contiguous: B + n*ldb + k
@@ -24,8 +27,12 @@ struct Problem {
   int32_t lda, ldb, ldc;
   int32_t tile_begin; // id of this problem's first output tile in the launch
   int32_t tiles_n;    // tile columns of this problem (tiles cover the valid extents only)
+  int32_t join_count; // contributions per output tile; 0 or 1: this problem alone
+  int32_t join_slot;  // this problem's place in the order of summation
+  int32_t join_first; // index, among all joined output tiles of the launch, of this problem's tile 0
+  int32_t pad;
 };
-static_assert(sizeof(Problem) == 64, "device layout");
+static_assert(sizeof(Problem) == 80, "device layout");
 
 // A rectangle of a problem's static output block that no output tile covers (whole tile rows / columns beyond the
 // valid extents): written as 0 by a fill kernel, so that the contraction kernel is launched over live tiles only.
@@ -77,11 +84,13 @@ int32_t plan_partition(const gspmd_mesh* mesh, const DotRoles& roles,
                        int64_t pid, const int64_t* lhs_fill, void* c_override,
                        std::vector<Problem>* problems, int64_t* out_static_elems, int32_t* layout);
 
-// Number of problems plan_partition would emit and the static out shard elements.
+// Upper bound of the number of problems plan_partition would emit, the static out shard elements and (if
+// `max_tiles` is non-null) an upper bound of the number of `tile` x `tile` output tiles of those problems: whatever
+// the buffers' row strides allow to be flattened, a flattened problem has no more tiles than its pieces.
 int32_t count_partition(const gspmd_mesh* mesh, const DotRoles& roles,
                         const gspmd_sharding* lhs_sh, const gspmd_sharding* rhs_sh,
                         const gspmd_sharding* out_sh, int64_t pid,
-                        int64_t* n_problems, int64_t* out_static_elems);
+                        int64_t* n_problems, int64_t* out_static_elems, int64_t* max_tiles = nullptr, int tile = 256);
 
 inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 

@@ -12,7 +12,7 @@ import paper_2105_04663_amd as g
 import workloads as wl
 from oracle import bounds as ob
 from oracle import dot as od
-from tests.harness import Staged, to_f64
+from tests.harness import Staged, out_tensor, to_f64
 
 pytestmark = pytest.mark.gpu
 
@@ -158,6 +158,39 @@ def test_contracting_split_local_partials_and_reduce():
     g.reduce_partials([t.data_ptr() for t in parts], n, outb.data_ptr(), g.BF16, torch.cuda.current_stream().cuda_stream)
     torch.cuda.synchronize()
     assert torch.equal(outb, out.to(torch.bfloat16))     # round-to-nearest-even of the fp32 sum
+
+
+@pytest.mark.parametrize("share", [True, False], ids=["one_launch", "two_launches"])
+@pytest.mark.parametrize("M,K,N,P", [(600, 2000, 520, 4), (256, 384, 256, 3), (70, 4100, 300, 8)])
+def test_sum_of_partials_is_the_ascending_fp32_sum(share, M, K, N, P):
+    # N(0,1) data, so the order of the fp32 additions shows in the last bits: whichever way the grouped call sums
+    # (members sharing one out buffer are joined in one launch, whichever workgroup arrives last doing the additions;
+    # members with out buffers of their own go through dense partials and a second kernel), the result must be
+    # ((p0 + p1) + p2) + ... in fp32, p_i being partition i's own partial product as gspmd_local_dot returns it.
+    w = wl.ksplit(M=M, K=K, N=N, P=P)
+    lhs, rhs = wl.draw_normal_bf16(5, w.lhs_shape), wl.draw_normal_bf16(6, w.rhs_shape)
+    st = Staged(w, lhs, rhs, row_align=8, out_dtype="f32", share_replicas=share)
+    if not share:      # replicated operands are still shared in this harness mode only for the outputs' sake
+        assert len({st.out[p][1].data_ptr() for p in range(P)}) == P
+    parts = []
+    for pid in range(P):
+        tmp = torch.full((M * st.out[pid][2],), float("nan"), device="cuda")
+        st.run_local(pid, out_override=g.ShardBuf.of(tmp, st.out[pid][2]))
+        torch.cuda.synchronize()
+        parts.append(tmp.view(M, -1)[:, :N].cpu().numpy())
+    want = parts[0].copy()
+    for q in parts[1:]:
+        want = want + q                                   # float32 + float32, ascending partition order
+    assert want.dtype == np.float32
+    for rep in range(3):                                  # arrival order varies from run to run; the sum must not
+        for p in range(P):
+            st.out[p][1].fill_(float("nan"))
+        st.run_grouped()
+        torch.cuda.synchronize()
+        for p in range(P):
+            got = out_tensor(st, p).cpu().numpy()
+            assert np.array_equal(got, want), f"rep {rep} partition {p}"
+    check(want.astype(np.float64), oracle_global(w, lhs, rhs), what="sum of partials against the oracle")
 
 
 # --------------------------------------------------------------------------- MoE fill counts

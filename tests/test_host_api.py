@@ -103,7 +103,7 @@ def test_classification_of_the_papers_examples():
     assert g.classify_dot(MESH, ffn2, S((8, 16, 128), (0, -1, 1)), S((128, 64), (1, -1)), S((8, 16, 64), (0, -1, 1))) == (g.AXIS_LHS_FREE, g.AXIS_CONTRACTING_SCATTER)
     # its workspace holds partials with M whole: 32 partitions x [2, 16, 64] fp32
     n = g.dot_workspace_bytes(MESH, ffn2, S((8, 16, 128), (0, -1, 1)), S((128, 64), (1, -1)), S((8, 16, 64), (0, -1, 1)), -1)
-    assert n == 32 * 2 * 128 + 32 * 2 * 16 * 64 * 4     # tables (up to one problem per B index) + partials
+    assert n == 32 * 2 * 144 + 32 * 2 * 16 * 64 * 4     # tables (up to one problem per B index) + partials
 
 
 @pytest.mark.parametrize("lhs,rhs,out", [
@@ -140,16 +140,17 @@ def test_size_one_mesh_dim_splits_nothing():
     assert g.classify_dot(mesh, ffn, S((8, 16, 64), (0, -1, -1)), S((64, 128), (-1, 1)), S((8, 16, 128), (0, -1, 1))) == (g.AXIS_UNUSED, g.AXIS_UNUSED)
     # a contracting dimension mapped to a size-1 mesh dimension needs no partial sums (and no partial buffers)
     assert g.classify_dot(mesh, ffn, S((8, 16, 64), (0, -1, 1)), S((64, 128), (1, -1)), S((8, 16, 128), (0, -1, -1))) == (g.AXIS_UNUSED, g.AXIS_UNUSED)
-    assert g.dot_workspace_bytes(mesh, ffn, S((8, 16, 64), (0, -1, 1)), S((64, 128), (1, -1)), S((8, 16, 128), (0, -1, -1)), -1) == 1024
+    assert g.dot_workspace_bytes(mesh, ffn, S((8, 16, 64), (0, -1, 1)), S((64, 128), (1, -1)), S((8, 16, 128), (0, -1, -1)), -1) == 1280     # 8 problems' tables, nothing else
 
 
 def test_workspace_query():
     n_local = g.dot_workspace_bytes(MESH, MM, S((6000, 12288), (0, -1)), S((12288, 10000), (-1, 1)), S((6000, 10000), (0, 1)), 3)
     n_all = g.dot_workspace_bytes(MESH, MM, S((6000, 12288), (0, -1)), S((12288, 10000), (-1, 1)), S((6000, 10000), (0, 1)), -1)
-    assert n_local == 256 and n_all == 32 * 128      # 128 bytes of launch tables per GEMM problem
+    assert n_local == 256 and n_all == 32 * 144      # 144 bytes of launch tables per GEMM problem
     mesh = g.Mesh((4,), (0, 1, 2, 3))
     n_k = g.dot_workspace_bytes(mesh, MM, S((4096, 16384), (-1, 0)), S((16384, 8192), (0, -1)), S((4096, 8192), (-1, -1)), -1)
-    assert n_k == 512 + 4 * 4096 * 8192 * 4     # tables + four fp32 partials
+    # tables + four fp32 partials, kept as one 256 x 256 slot per output tile and partition with a counter per slot
+    assert n_k == 768 + 4 * 512 * 4 + 4 * 4096 * 8192 * 4
 
 
 def test_device_calls_validate_before_touching_the_gpu():
