@@ -109,7 +109,8 @@ typedef struct {
  * row_stride: distance in elements between consecutive indices of the second-to-last
  * dimension; 0 means dense (= static size of the last dimension).  Outer dimensions are
  * dense on top of it.  A row_stride that is a multiple of 8 elements together with a
- * 16-byte aligned pointer selects the MFMA kernels for bf16; an operand whose contiguous dimension
+ * 16-byte aligned pointer selects the fastest MFMA kernel for bf16 (an even row_stride with a 4-byte aligned pointer
+ * its register-staged variant, see gspmd_kernel_path); an operand whose contiguous dimension
  * is contracted runs fastest when its rows start on 128-byte lines (row_stride a multiple of 64
  * elements: 9 % faster than a multiple of 8 that is not, at 8200 against 8256).  data may be NULL only for a
  * tensor with a zero-size dimension (no elements: nothing is read or written). */
@@ -168,7 +169,18 @@ typedef struct {
   int32_t m_valid, n_valid, k_valid;
   int32_t m_static, n_static;
   int32_t layout;
+  int32_t kernel;   /* gspmd_kernel_path of a launch made of such GEMMs, for bf16 operands at 16-byte aligned addresses */
+  int32_t reserved;
 } gspmd_gemm_desc;
+
+/* Which contraction kernel the leading dimensions allow (the slowest one any GEMM of a launch needs is used for
+ * the whole launch).  bf16 operands whose rows are not even 4-byte aligned, and fp32 operands, take the scalar kernel,
+ * which is a correctness path many times slower than the other two. */
+typedef enum {
+  GSPMD_KERNEL_SCALAR = 0,       /* 64 x 64 tiles, fp32 FMA */
+  GSPMD_KERNEL_MFMA_STAGED = 1,  /* MFMA, operand tiles through registers: lda and ldb even (rows 4-byte aligned) */
+  GSPMD_KERNEL_MFMA = 2          /* MFMA, direct global->LDS loads: lda and ldb multiples of 8 elements */
+} gspmd_kernel_path;
 
 /* Utility for inspection and tests: the per-partition program of Section 4 made explicit.
  * How gspmd_local_dot lowers partition `partition_id`'s Dot (shard bounds -> flattened batch / free / contracting

@@ -10,6 +10,7 @@ F32, BF16 = 0, 1
 AXIS_UNUSED, AXIS_BATCH, AXIS_LHS_FREE, AXIS_RHS_FREE, AXIS_CONTRACTING, AXIS_CONTRACTING_SCATTER = range(6)
 EPILOGUE_NONE, EPILOGUE_RELU = 0, 1
 LAYOUT_LHS_K_MAJOR, LAYOUT_RHS_K_CONTIGUOUS = 1, 2
+KERNEL_SCALAR, KERNEL_MFMA_STAGED, KERNEL_MFMA = 0, 1, 2
 
 EXPORTED_SYMBOLS = (
     "gspmd_status_string", "gspmd_shard_bounds", "gspmd_classify_dot", "gspmd_dot_workspace_bytes",
@@ -48,7 +49,8 @@ class _CGemmDesc(C.Structure):
     _fields_ = [("a_offset", C.c_int64), ("b_offset", C.c_int64), ("c_offset", C.c_int64),
                 ("lda", C.c_int64), ("ldb", C.c_int64), ("ldc", C.c_int64),
                 ("m_valid", C.c_int32), ("n_valid", C.c_int32), ("k_valid", C.c_int32),
-                ("m_static", C.c_int32), ("n_static", C.c_int32), ("layout", C.c_int32)]
+                ("m_static", C.c_int32), ("n_static", C.c_int32), ("layout", C.c_int32), ("kernel", C.c_int32),
+                ("reserved", C.c_int32)]
 
 
 _LIB = None

@@ -62,17 +62,28 @@ int64_t assign_tiles(std::vector<Problem>& ps, int bm, int bn) {
   return t;
 }
 
-bool mfma_eligible(const std::vector<Problem>& ps, int32_t in_dtype, int32_t layout) {
-  if (in_dtype != GSPMD_BF16) return false;
+// Which contraction kernel a launch can take: the MFMA kernel with direct global->LDS loads needs 16-byte aligned
+// operand pointers and leading dimensions that are multiples of 8 elements; its register-staged variant 4-byte aligned
+// pointers and even leading dimensions; anything else (and fp32 operands) goes to the scalar-FMA kernel.
+enum KernelPath { kPathFallback = 0, kPathMfmaStaged = 1, kPathMfmaDirect = 2 };
+
+KernelPath kernel_path(const std::vector<Problem>& ps, int32_t in_dtype, int32_t layout, bool check_pointers = true) {
+  if (in_dtype != GSPMD_BF16) return kPathFallback;
   // 32-bit byte offsets inside a tile: 256 rows of a K-contiguous operand, 32 of a K-major one
   const int32_t max_lda = (layout & GSPMD_LAYOUT_LHS_K_MAJOR) ? (1 << 24) : (1 << 22);
   const int32_t max_ldb = (layout & GSPMD_LAYOUT_RHS_K_CONTIGUOUS) ? (1 << 22) : (1 << 24);
+  KernelPath path = kPathMfmaDirect;
   for (const auto& p : ps) {
-    if ((reinterpret_cast<uintptr_t>(p.A) | reinterpret_cast<uintptr_t>(p.B)) & 15) return false;
-    if ((p.lda & 7) || (p.ldb & 7)) return false;
-    if (p.lda > max_lda || p.ldb > max_ldb) return false;
+    const uintptr_t ptrs = check_pointers ? reinterpret_cast<uintptr_t>(p.A) | reinterpret_cast<uintptr_t>(p.B) : 0;
+    if (p.lda > max_lda || p.ldb > max_ldb) return kPathFallback;
+    if ((ptrs & 3) || ((p.lda | p.ldb) & 1)) return kPathFallback;
+    if ((ptrs & 15) || ((p.lda | p.ldb) & 7)) path = kPathMfmaStaged;
   }
-  return true;
+  return path;
+}
+
+bool mfma_eligible(const std::vector<Problem>& ps, int32_t in_dtype, int32_t layout) {
+  return kernel_path(ps, in_dtype, layout) != kPathFallback;
 }
 
 // Run the contraction over all live tiles, then the zero fill of what the tiles do not cover.  Output tiles cover
@@ -106,7 +117,8 @@ int32_t launch_problems(std::vector<Problem>& all, int32_t layout, int32_t in_dt
   if (in_dtype == GSPMD_F32 && out_dtype != GSPMD_F32) return GSPMD_ERR_UNSUPPORTED;
   std::vector<Problem> ps;
   for (const auto& p : all) if (p.Mv > 0) ps.push_back(p);      // Mv, Nv, Kv are all zero or all positive
-  const bool mfma = mfma_eligible(ps, in_dtype, layout);
+  const KernelPath path = kernel_path(ps, in_dtype, layout);
+  const bool mfma = path != kPathFallback;
   if (join && !mfma) return GSPMD_ERR_UNSUPPORTED;              // the caller checks before it joins problems
   const int bm = mfma ? kMfmaBM : kGenTile, bn = mfma ? kMfmaBN : kGenTile;
   const int64_t tiles = assign_tiles(ps, bm, bn);
@@ -152,7 +164,7 @@ int32_t launch_problems(std::vector<Problem>& all, int32_t layout, int32_t in_dt
         hipLaunchKernelGGL(zero_words_kernel, dim3(blocks), dim3(256), 0, stream, join->counters, join->tiles);
         if (hipGetLastError() != hipSuccess) return GSPMD_ERR_DEVICE;
       }
-      if (!launch_dot_mfma(inl, tab, n, static_cast<int>(tiles), layout, out_dtype, epilogue, join ? join->partials : nullptr,
+      if (!launch_dot_mfma(inl, tab, n, static_cast<int>(tiles), layout, out_dtype, path == kPathMfmaStaged, epilogue, join ? join->partials : nullptr,
                            join ? join->counters : nullptr, stream)) return GSPMD_ERR_DEVICE;
     } else {
       const dim3 grid(static_cast<unsigned>(tiles)), block(256);
@@ -427,6 +439,11 @@ int32_t gspmd_plan_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
   int32_t layout = 0;
   if ((st = plan_partition(mesh, r, &la, lhs_sh, &rb, rhs_sh, &oc, out_sh, pid, lhs_fill, nullptr, &ps, &elems, &layout)) != GSPMD_OK) return st;
   *count = static_cast<int64_t>(ps.size());
+  // the operand addresses here are made up: the path is named from the leading dimensions alone
+  std::vector<Problem> live;
+  for (const auto& p : ps) if (p.Mv > 0) live.push_back(p);
+  const KernelPath kp = kernel_path(live, GSPMD_BF16, layout, false);
+  const int32_t path = kp == kPathMfmaDirect ? GSPMD_KERNEL_MFMA : kp == kPathMfmaStaged ? GSPMD_KERNEL_MFMA_STAGED : GSPMD_KERNEL_SCALAR;
   for (int64_t i = 0; i < std::min<int64_t>(capacity, *count); ++i) {
     const Problem& p = ps[static_cast<size_t>(i)];
     gspmd_gemm_desc& d = descs[i];
@@ -437,6 +454,8 @@ int32_t gspmd_plan_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
     d.m_valid = p.Mv; d.n_valid = p.Nv; d.k_valid = p.Kv;
     d.m_static = p.Ms; d.n_static = p.Ns;
     d.layout = layout;
+    d.kernel = path;
+    d.reserved = 0;
   }
   return GSPMD_OK;
 } catch (...) { return GSPMD_ERR_HOST_MEMORY; }

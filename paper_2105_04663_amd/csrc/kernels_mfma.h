@@ -65,7 +65,15 @@ __device__ __forceinline__ u32x4_t mask_tail8(u32x4_t v, int keep) {   // keep f
   return v;
 }
 
-template <typename TOut, int LAYOUT>
+// 16 bytes from an address that is only 4-byte aligned
+struct __attribute__((packed, aligned(4))) Words4 { uint32_t w[4]; };
+
+// STAGED: the variant for operands whose rows are only 4-byte aligned (an even row stride that is not a multiple of
+// 8 elements, e.g. dense shards of 1250 columns): direct global->LDS loads need 16-byte aligned chunks, so every K
+// tile goes through registers instead -- the path the other variant uses for what is left of K after its assembly
+// loop -- with the next K step's chunks in flight while the current one is multiplied.  Chunks that are only partly
+// valid are loaded 4 bytes at a time, so that no read leaves the rows' valid part by more than one element.
+template <typename TOut, int LAYOUT, bool STAGED>
 __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const InlineProblems inl, const Problem* __restrict__ tab, int n_prob, int epilogue,
                                                                 float* __restrict__ join_partials, uint32_t* __restrict__ join_counters) {
   constexpr bool AKM = (LAYOUT & GSPMD_LAYOUT_LHS_K_MAJOR) != 0, BKC = (LAYOUT & GSPMD_LAYOUT_RHS_K_CONTIGUOUS) != 0;
@@ -127,17 +135,43 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const InlineProb
       for (int j = 0; j < 4; ++j) global_to_lds16(bb, b_off[j], sa + kStageA + j * 1024);
     };
     // one 16-byte chunk of a K tile that may be partial: into a register, zero where it lies beyond the valid K (in
-    // BOTH operands: the padding may hold anything)
-    auto tail_chunk = [&](bool kmajor, const bf16_bits* base, int off, int q, int k0) -> u32x4_t {
+    // BOTH operands: the padding may hold anything).  `cols_valid`: valid columns of a K-major operand, counted like
+    // `c0`, the tile's first column.
+    auto tail_chunk = [&](bool kmajor, const bf16_bits* base, int off, int q, int k0, int c0, int cols_valid) -> u32x4_t {
       u32x4_t v = {0u, 0u, 0u, 0u};
+      const unsigned char* at = reinterpret_cast<const unsigned char*>(base) + off;
       if (kmajor) {         // a whole k row per 32 lanes
         const int kr = k0 + q * 2 + (lane >> 5);
-        if (kr < P.Kv) v = *reinterpret_cast<const u32x4_t*>(reinterpret_cast<const unsigned char*>(base) + off);
+        if (kr < P.Kv) {
+          if constexpr (!STAGED) {
+            v = *reinterpret_cast<const u32x4_t*>(at);
+          } else {
+            int n = c0 + (((lane & 31) ^ swz_b(q * 2 + (lane >> 5))) << 3);    // the chunk km_load_offset addresses
+            if (n >= cols_valid) n = ((cols_valid - 1) >> 3) << 3;
+            if (n + 8 <= cols_valid) {
+              const Words4 w = *reinterpret_cast<const Words4*>(at);
+              v = u32x4_t{w.w[0], w.w[1], w.w[2], w.w[3]};
+            } else {
+#pragma unroll
+              for (int d = 0; d < 4; ++d)
+                if (n + 2 * d < cols_valid) v[d] = *reinterpret_cast<const uint32_t*>(at + 4 * d);
+            }
+          }
+        }
       } else {              // 8 consecutive k per lane
         const int r = q * 16 + (lane >> 2);
         const int k = k0 + ((lane & 3) ^ swz_a(r)) * 8;
         if (k < P.Kv) {
-          v = *reinterpret_cast<const u32x4_t*>(reinterpret_cast<const unsigned char*>(base) + off);
+          if constexpr (!STAGED) {
+            v = *reinterpret_cast<const u32x4_t*>(at);
+          } else if (k + 8 <= P.Kv) {
+            const Words4 w = *reinterpret_cast<const Words4*>(at);
+            v = u32x4_t{w.w[0], w.w[1], w.w[2], w.w[3]};
+          } else {
+#pragma unroll
+            for (int d = 0; d < 4; ++d)
+              if (k + 2 * d < P.Kv) v[d] = *reinterpret_cast<const uint32_t*>(at + 4 * d);
+          }
           if (k + 8 > P.Kv) v = mask_tail8(v, P.Kv - k);
         }
       }
@@ -154,8 +188,8 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const InlineProb
         const int q = wn * 4 + j;
         const int ao = AKM ? km_load_offset(q, lane, m0, m_end, P.lda) : kc_load_offset(q, lane, m0, m_end, P.lda);
         const int bo = BKC ? kc_load_offset(q, lane, n0, P.Nv, P.ldb) : km_load_offset(q, lane, n0, P.Nv, P.ldb);
-        ta[j] = tail_chunk(AKM, ab, ao, q, k0);
-        tb[j] = tail_chunk(!BKC, bb, bo, q, k0);
+        ta[j] = tail_chunk(AKM, ab, ao, q, k0, m0, m_end);
+        tb[j] = tail_chunk(!BKC, bb, bo, q, k0, n0, P.Nv);
       }
     };
     auto store_tail = [&](int stage, const u32x4_t (&ta)[4], const u32x4_t (&tb)[4]) {
@@ -199,6 +233,26 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const InlineProb
         }
     };
 
+    if constexpr (STAGED) {
+      // ---- every K tile through registers, two tiles (one per wave group) per step; the next step's chunks are in
+      // flight while this step is multiplied
+      const int ntiles = (P.Kv + kMfmaBK - 1) / kMfmaBK;
+      u32x4_t ta[4], tb[4];
+      if (wm < ntiles) fetch_tail(wm, ta, tb);
+      for (int kt = 0; kt < ntiles; kt += 2) {
+        const int here = min(2, ntiles - kt);
+        if (wm < here) store_tail(wm, ta, tb);
+        __syncthreads();
+        if (kt + 2 + wm < ntiles) fetch_tail(kt + 2 + wm, ta, tb);
+        read_frags(0);
+        mma_all();
+        if (here > 1) {
+          read_frags(1);
+          mma_all();
+        }
+        __syncthreads();
+      }
+    } else {
     if (nk64 > 0) {
       // ---- prologue: group 0 loads tiles 0 and 2, group 1 tiles 1 and 3; tiles 0 and 1 must have landed
       load_tile(wm);
@@ -289,6 +343,7 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const InlineProb
         __syncthreads();
       }
     }
+    }   // !STAGED
   }
 
   // ---- joined problems (a contracting dimension split over partitions, Section 4.2, or one K range cut in pieces):
@@ -451,7 +506,7 @@ constexpr int kMaxDevices = 64;
 
 // The kernel needs all 160 KiB of LDS as dynamic shared memory: raised once per instantiation and device.  Callable
 // from several host threads.
-template <typename TOut, int LAYOUT>
+template <typename TOut, int LAYOUT, bool STAGED>
 inline bool launch_dot_mfma_as(const InlineProblems& inl, const Problem* tab, int n_prob, int tiles, int epilogue, float* join_partials,
                                uint32_t* join_counters, hipStream_t stream) {
   static std::once_flag once[kMaxDevices];
@@ -459,24 +514,35 @@ inline bool launch_dot_mfma_as(const InlineProblems& inl, const Problem* tab, in
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return false;
   std::call_once(once[dev], [dev] {
-    ok[dev] = hipFuncSetAttribute(reinterpret_cast<const void*>(&dot_mfma_kernel<TOut, LAYOUT>),
+    ok[dev] = hipFuncSetAttribute(reinterpret_cast<const void*>(&dot_mfma_kernel<TOut, LAYOUT, STAGED>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, kMfmaLds) == hipSuccess;
   });
   if (!ok[dev]) return false;
   const dim3 grid(static_cast<unsigned>(tiles)), block(kMfmaThreads);
-  hipLaunchKernelGGL((dot_mfma_kernel<TOut, LAYOUT>), grid, block, kMfmaLds, stream, inl, tab, n_prob, epilogue, join_partials, join_counters);
+  hipLaunchKernelGGL((dot_mfma_kernel<TOut, LAYOUT, STAGED>), grid, block, kMfmaLds, stream, inl, tab, n_prob, epilogue, join_partials, join_counters);
   return hipGetLastError() == hipSuccess;
 }
 
-inline bool launch_dot_mfma(const InlineProblems& inl, const Problem* tab, int n_prob, int tiles, int32_t layout, int32_t out_dtype,
-                            int epilogue, float* join_partials, uint32_t* join_counters, hipStream_t stream) {
-  const bool f32 = out_dtype == GSPMD_F32;
+template <typename TOut, bool STAGED>
+inline bool launch_dot_mfma_layout(const InlineProblems& inl, const Problem* tab, int n_prob, int tiles, int32_t layout, int epilogue,
+                                   float* join_partials, uint32_t* join_counters, hipStream_t stream) {
   switch (layout & 3) {
-    case 0: return f32 ? launch_dot_mfma_as<float, 0>(inl, tab, n_prob, tiles, epilogue, join_partials, join_counters, stream) : launch_dot_mfma_as<bf16_bits, 0>(inl, tab, n_prob, tiles, epilogue, join_partials, join_counters, stream);
-    case 1: return f32 ? launch_dot_mfma_as<float, 1>(inl, tab, n_prob, tiles, epilogue, join_partials, join_counters, stream) : launch_dot_mfma_as<bf16_bits, 1>(inl, tab, n_prob, tiles, epilogue, join_partials, join_counters, stream);
-    case 2: return f32 ? launch_dot_mfma_as<float, 2>(inl, tab, n_prob, tiles, epilogue, join_partials, join_counters, stream) : launch_dot_mfma_as<bf16_bits, 2>(inl, tab, n_prob, tiles, epilogue, join_partials, join_counters, stream);
-    default: return f32 ? launch_dot_mfma_as<float, 3>(inl, tab, n_prob, tiles, epilogue, join_partials, join_counters, stream) : launch_dot_mfma_as<bf16_bits, 3>(inl, tab, n_prob, tiles, epilogue, join_partials, join_counters, stream);
+    case 0: return launch_dot_mfma_as<TOut, 0, STAGED>(inl, tab, n_prob, tiles, epilogue, join_partials, join_counters, stream);
+    case 1: return launch_dot_mfma_as<TOut, 1, STAGED>(inl, tab, n_prob, tiles, epilogue, join_partials, join_counters, stream);
+    case 2: return launch_dot_mfma_as<TOut, 2, STAGED>(inl, tab, n_prob, tiles, epilogue, join_partials, join_counters, stream);
+    default: return launch_dot_mfma_as<TOut, 3, STAGED>(inl, tab, n_prob, tiles, epilogue, join_partials, join_counters, stream);
   }
+}
+
+// `staged`: the operands allow 4-byte but not 16-byte aligned chunk loads
+inline bool launch_dot_mfma(const InlineProblems& inl, const Problem* tab, int n_prob, int tiles, int32_t layout, int32_t out_dtype,
+                            bool staged, int epilogue, float* join_partials, uint32_t* join_counters, hipStream_t stream) {
+  const bool f32 = out_dtype == GSPMD_F32;
+  if (staged)
+    return f32 ? launch_dot_mfma_layout<float, true>(inl, tab, n_prob, tiles, layout, epilogue, join_partials, join_counters, stream)
+               : launch_dot_mfma_layout<bf16_bits, true>(inl, tab, n_prob, tiles, layout, epilogue, join_partials, join_counters, stream);
+  return f32 ? launch_dot_mfma_layout<float, false>(inl, tab, n_prob, tiles, layout, epilogue, join_partials, join_counters, stream)
+             : launch_dot_mfma_layout<bf16_bits, false>(inl, tab, n_prob, tiles, layout, epilogue, join_partials, join_counters, stream);
 }
 
 }  // namespace gspmd

@@ -94,15 +94,19 @@ def test_config4_moe_full_size():
         check(to_f64(out[e].contiguous()), ref, f"config 4 expert {e}")
 
 
-@pytest.mark.parametrize("make", [wl.mesh2d, wl.mesh2d_uneven], ids=["config5", "config5_uneven"])
-def test_config5_nested_mesh_full_size(make):
+@pytest.mark.parametrize("make,row_align", [(wl.mesh2d, 8), (wl.mesh2d_uneven, 8), (wl.mesh2d, 0)],
+                         ids=["config5", "config5_uneven", "config5_dense_rows"])
+def test_config5_nested_mesh_full_size(make, row_align):
+    # row_align 0: the 1250-column shards stored densely, rows 4-byte aligned only -> the register-staged MFMA kernel
+    import paper_2105_04663_amd as g
     w = make()
     lhs, rhs = w.draw_lhs(), w.draw_rhs()
-    st = Staged(w, lhs, rhs, row_align=8)
+    st = Staged(w, lhs, rhs, row_align=row_align)
+    want_kernel = g.KERNEL_MFMA if row_align else g.KERNEL_MFMA_STAGED
+    assert g.plan_dot(st.mesh, st.dims, st.lhs_sh, st.rhs_sh, st.out_sh, 13, st.lhs[13][2], st.rhs[13][2], st.out[13][2])[0]["kernel"] == want_kernel
     st.run_grouped()
     M, N = w.out_shape
     glob = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
-    import paper_2105_04663_amd as g
     for pid in range(32):
         off, valid, shard = g.shard_bounds(st.mesh, st.out_sh, pid)
         assert (off, valid, shard) == ob.shard_bounds(w.mesh_shape, w.device_ids, w.out_shape, w.out_map, pid)

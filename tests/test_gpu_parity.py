@@ -364,6 +364,27 @@ def test_two_contracting_dims_and_batch_fp32():
         check(st.out_shard(pid), ref, fro_tol=1e-5)
 
 
+@pytest.mark.parametrize("layout", ["nn", "tn", "nt", "tt"])
+@pytest.mark.parametrize("M,K,N", [(300, 1250, 258), (530, 202, 1250), (64, 70, 66)])
+def test_rows_that_are_only_4_byte_aligned_take_the_staged_mfma_kernel(layout, M, K, N):
+    # dense rows of an even length that is not a multiple of 8 elements (the 1250-column shards of the 4 x 8 mesh when
+    # stored without row padding): the MFMA kernel's register-staged variant.  NaN around every shard, integer operands,
+    # exact result; the out shards' own padding (uneven split) must be zero.
+    if layout == "nn":
+        w = _generic((M, K), (K, N), (), (), (1,), (0,), (2,), (0, -1), (-1, -1), (0, -1), out_dtype="f32")
+    else:
+        w = _layout_workload(layout, M, K, N, mesh_shape=(2,), lmap=(0, -1) if layout == "nt" else (-1, 0), omap=(0, -1), out_dtype="f32")
+    lhs, rhs = wl.draw_small_int_bf16(21, w.lhs_shape), wl.draw_small_int_bf16(22, w.rhs_shape)
+    st = Staged(w, lhs, rhs, row_align=2, out_dtype="f32")
+    descs = g.plan_dot(st.mesh, st.dims, st.lhs_sh, st.rhs_sh, st.out_sh, 0, st.lhs[0][2], st.rhs[0][2], st.out[0][2])
+    assert all(d["kernel"] == g.KERNEL_MFMA_STAGED for d in descs), [(d["lda"], d["ldb"]) for d in descs]
+    st.run_grouped()
+    ref = oracle_global(w, lhs, rhs)
+    for pid in range(st.P):
+        want = od.expected_out_shard(ref, w.mesh_shape, w.device_ids, w.out_map, pid)
+        assert np.array_equal(st.out_shard(pid), want), f"partition {pid}"
+
+
 # --------------------------------------------------------------------------- backward-pass layouts
 LAYOUTS = {  # name -> (lhs shape from (M,K), rhs shape from (K,N), lhs contracting dim, rhs contracting dim)
     "tn": (lambda M, K: (K, M), lambda K, N: (K, N), 0, 0),     # weight gradient: both operands K-major

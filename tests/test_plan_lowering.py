@@ -159,6 +159,13 @@ def test_config_lowerings():
     d = g.plan_dot(g.Mesh(w.mesh_shape, w.device_ids), g.DotDims((), (), (1,), (0,)), g.Sharding(w.lhs_shape, w.lhs_map),
                    g.Sharding(w.rhs_shape, w.rhs_map), g.Sharding(w.out_shape, w.out_map), 13, 0, 1256, 1256)
     assert len(d) == 1 and (d[0]["m_valid"], d[0]["n_valid"], d[0]["k_valid"], d[0]["ldb"], d[0]["ldc"]) == (1500, 1250, 12288, 1256, 1256)
+    assert d[0]["kernel"] == g.KERNEL_MFMA
+    # the same partition with dense rows: 1250-element rows are 4-byte but not 16-byte aligned -> the register-staged
+    # MFMA variant; a dimension of 1251 would leave rows 2-byte aligned -> the scalar kernel
+    args = (g.Mesh(w.mesh_shape, w.device_ids), g.DotDims((), (), (1,), (0,)), g.Sharding(w.lhs_shape, w.lhs_map),
+            g.Sharding(w.rhs_shape, w.rhs_map), g.Sharding(w.out_shape, w.out_map), 13)
+    assert g.plan_dot(*args)[0]["kernel"] == g.KERNEL_MFMA_STAGED and g.plan_dot(*args)[0]["ldb"] == 1250
+    assert g.plan_dot(*args, 0, 1251, 1251)[0]["kernel"] == g.KERNEL_SCALAR
 
 
 def _check_all_partitions(lhs, rhs, dims, mshape, ids, lmap, rmap, omap, fill=None, fill_dim=None):
