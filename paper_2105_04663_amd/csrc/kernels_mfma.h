@@ -66,7 +66,7 @@ __device__ __forceinline__ u32x4_t mask_tail8(u32x4_t v, int keep) {   // keep f
 }
 
 // 16 bytes from an address that is only 4-byte aligned
-struct __attribute__((packed, aligned(4))) Words4 { uint32_t w[4]; };
+typedef uint32_t u32x4_align4_t __attribute__((ext_vector_type(4), aligned(4)));
 
 // STAGED: the variant for operands whose rows are only 4-byte aligned (an even row stride that is not a multiple of
 // 8 elements, e.g. dense shards of 1250 columns): direct global->LDS loads need 16-byte aligned chunks, so every K
@@ -139,22 +139,24 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const InlineProb
     // `c0`, the tile's first column.
     auto tail_chunk = [&](bool kmajor, const bf16_bits* base, int off, int q, int k0, int c0, int cols_valid) -> u32x4_t {
       u32x4_t v = {0u, 0u, 0u, 0u};
-      const unsigned char* at = reinterpret_cast<const unsigned char*>(base) + off;
+      // operands live in global memory: loads through a global (not generic) pointer count in vmcnt only, so waiting for
+      // LDS reads does not wait for them
+      typedef __attribute__((address_space(1))) const unsigned char* gptr_t;
+      gptr_t at = (gptr_t)(reinterpret_cast<const unsigned char*>(base) + off);
       if (kmajor) {         // a whole k row per 32 lanes
         const int kr = k0 + q * 2 + (lane >> 5);
         if (kr < P.Kv) {
           if constexpr (!STAGED) {
-            v = *reinterpret_cast<const u32x4_t*>(at);
+            v = *(__attribute__((address_space(1))) const u32x4_t*)at;
           } else {
             int n = c0 + (((lane & 31) ^ swz_b(q * 2 + (lane >> 5))) << 3);    // the chunk km_load_offset addresses
             if (n >= cols_valid) n = ((cols_valid - 1) >> 3) << 3;
             if (n + 8 <= cols_valid) {
-              const Words4 w = *reinterpret_cast<const Words4*>(at);
-              v = u32x4_t{w.w[0], w.w[1], w.w[2], w.w[3]};
+              v = *(__attribute__((address_space(1))) const u32x4_align4_t*)at;
             } else {
 #pragma unroll
               for (int d = 0; d < 4; ++d)
-                if (n + 2 * d < cols_valid) v[d] = *reinterpret_cast<const uint32_t*>(at + 4 * d);
+                if (n + 2 * d < cols_valid) v[d] = *(__attribute__((address_space(1))) const uint32_t*)(at + 4 * d);
             }
           }
         }
@@ -163,14 +165,13 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const InlineProb
         const int k = k0 + ((lane & 3) ^ swz_a(r)) * 8;
         if (k < P.Kv) {
           if constexpr (!STAGED) {
-            v = *reinterpret_cast<const u32x4_t*>(at);
+            v = *(__attribute__((address_space(1))) const u32x4_t*)at;
           } else if (k + 8 <= P.Kv) {
-            const Words4 w = *reinterpret_cast<const Words4*>(at);
-            v = u32x4_t{w.w[0], w.w[1], w.w[2], w.w[3]};
+            v = *(__attribute__((address_space(1))) const u32x4_align4_t*)at;
           } else {
 #pragma unroll
             for (int d = 0; d < 4; ++d)
-              if (k + 2 * d < P.Kv) v[d] = *reinterpret_cast<const uint32_t*>(at + 4 * d);
+              if (k + 2 * d < P.Kv) v[d] = *(__attribute__((address_space(1))) const uint32_t*)(at + 4 * d);
           }
           if (k + 8 > P.Kv) v = mask_tail8(v, P.Kv - k);
         }
