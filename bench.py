@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the per-partition einsum hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--headline-only]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--headline-only] [--only NAME] [--calibrate-copy] [--probe-power]
 
 A step is one pass of the hot path over the Transformer feed-forward share
 (BSM,MH->BSH, B=8 S=2048 M=8192 H_local=8192, bf16 operands, fp32 accumulate, bf16 out):
@@ -28,6 +28,8 @@ PEAK_HBM_GBS = 8000.0
 # L2 <-> fabric bytes of one dot_mfma_kernel launch on the FFN share, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled
 # by a copy kernel of known size (profiles/dot_mfma_kernel_ffn_share.md): 3.224e9 fetched + 0.268e9 written
 FFN_TRAFFIC_BYTES = 3.224e9 + 0.268e9
+FFN_TRAFFIC_SOURCE = ("profiles/dot_mfma_kernel_ffn_share.md: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE per dispatch, scaled by "
+                      "bench.py --calibrate-copy; a profiler figure quoted here, not measured by this run")
 METRIC = "per-shard einsum bf16 TFLOP/s and % of MI355X MFMA peak (1 GPU)"
 
 
@@ -41,6 +43,10 @@ def parse():
     ap.add_argument("--cpu-rows", type=int, default=16384, help="rows of the FFN output the CPU oracle is timed on")
     ap.add_argument("--only", default=None,
                     help="time just one of the other workloads (by name, e.g. moe_ecm_emh) and print its entry; for profiling")
+    ap.add_argument("--probe-power", action="store_true",
+                    help="run only the power probe: the headline kernel looped for 4 s on the benchmark's data and on all-zero "
+                         "operands, with the shader clock and package power sampled from rocm-smi (the kernel is power-limited: "
+                         "same cycles per launch, different clock)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain copy of known size (shard_extract of a [16384,8192] bf16 tensor on a 1-partition "
                          "mesh: 268435456 bytes read, 268435456 written per launch) for scaling HBM byte counters")
@@ -219,12 +225,44 @@ def main():
         fl = ww.useful_flops(s2.fill)
         entry = {"ms_per_step": round(wall, 4), "tflops": round(fl / (wall * 1e-3) / 1e12, 2),
                  "pct_of_peak": round(100.0 * fl / (wall * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 2), "useful_flops": fl,
-                 "einsum": ww.einsum, "partitions": ww.n_partitions}
+                 "einsum": ww.einsum, "partitions": ww.n_partitions,
+                 # the step's device time between two events on the launch stream: the contraction kernel plus, where the
+                 # workload has them, the zero fill and the sum of partials
+                 "roofline": {"bound": "mfma", "achieved": round(fl / (ev * 1e-3) / 1e12, 2), "peak": PEAK_BF16_TFLOPS,
+                              "unit": "TFLOP/s", "frac": round(fl / (ev * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4), "flops": fl,
+                              "kernel": "dot_mfma_kernel", "device_ms": round(ev, 4)}}
         if s2.fill is not None:
             entry["fill"] = [int(x) for x in s2.fill]
         del s2
         torch.cuda.empty_cache()
         return entry
+
+    if args.probe_power:
+        w = wl.ffn()
+        st = Staged(w)
+        flops = w.useful_flops()
+        out = {"probe": "power", "workload": w.einsum, "seconds_per_case": 4.0}
+        for tag in ("benchmark_data", "all_zero_operands"):
+            if tag == "all_zero_operands":
+                for x in st.lhs + st.rhs:
+                    x[1].zero_()
+            for _ in range(40):
+                st.step()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            n_steps = [0]
+
+            def counted():
+                n_steps[0] += 1
+                st.step()
+            e0.record()
+            load = sample_clock_under_load(counted, torch, seconds=4.0)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / max(n_steps[0], 1)
+            out[tag] = {"ms_per_launch": round(ms, 4), "tflops": round(flops / ms / 1e9, 1), "launches": n_steps[0], "rocm_smi": load}
+        print(json.dumps(out), flush=True)
+        return
 
     if args.only:
         for make in other_makers:
@@ -270,6 +308,7 @@ def main():
         "pct_of_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
         "roofline": {"bound": "mfma", "achieved": round(kern_tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(kern_tflops / PEAK_BF16_TFLOPS, 4), "traffic": FFN_TRAFFIC_BYTES,
+                     "traffic_source": FFN_TRAFFIC_SOURCE,
                      "algorithmic_bytes": 16384 * 8192 * 2 + 8192 * 8192 * 2 + 16384 * 8192 * 2,
                      "kernel": "dot_mfma_kernel", "kernel_ms": round(ev_ms, 4),
                      "kernel_ms_median": round(per[len(per) // 2], 4), "kernel_ms_min": round(per[0], 4)},
@@ -338,7 +377,10 @@ def main():
         ms = timed_call(lambda: g.reduce_partials([t.data_ptr() for t in parts], n_el, red.data_ptr(), g.F32, stream), 20, 3)
         rbytes = 5 * n_el * 4
         others["ksplit_matmul"]["reduce_alone"] = {"kernel": "reduce_partials_kernel", "ms": round(ms, 4), "algorithmic_bytes": rbytes,
-                                                   "gbs": round(rbytes / ms / 1e6, 1), "frac_of_hbm_peak": round(rbytes / ms / 1e6 / PEAK_HBM_GBS, 3)}
+                                                   "gbs": round(rbytes / ms / 1e6, 1), "frac_of_hbm_peak": round(rbytes / ms / 1e6 / PEAK_HBM_GBS, 3),
+                                                   "roofline": {"bound": "hbm", "achieved": round(rbytes / ms / 1e6, 1), "peak": PEAK_HBM_GBS,
+                                                                "unit": "GB/s", "frac": round(rbytes / ms / 1e6 / PEAK_HBM_GBS, 4),
+                                                                "algorithmic_bytes": rbytes, "kernel": "reduce_partials_kernel"}}
         del parts, red
         # the contraction part of config 3 alone: the four partitions' partial products as one launch of four problems
         # (the partition index as a batch dimension), fp32 partials written, no sum
@@ -356,7 +398,10 @@ def main():
         pfl = 2.0 * 4 * 4096 * 4096 * 8192
         others["ksplit_matmul"]["gemm_alone"] = {"kernel": "dot_mfma_kernel (fp32 partials)", "ms": round(ms, 4),
                                                  "tflops": round(pfl / ms / 1e9, 2),
-                                                 "pct_of_peak": round(100.0 * pfl / ms / 1e9 / PEAK_BF16_TFLOPS, 2)}
+                                                 "pct_of_peak": round(100.0 * pfl / ms / 1e9 / PEAK_BF16_TFLOPS, 2),
+                                                 "roofline": {"bound": "mfma", "achieved": round(pfl / ms / 1e9, 2), "peak": PEAK_BF16_TFLOPS,
+                                                              "unit": "TFLOP/s", "frac": round(pfl / ms / 1e9 / PEAK_BF16_TFLOPS, 4),
+                                                              "flops": pfl, "kernel": "dot_mfma_kernel"}}
         del pa, pb, pc, pws
         mesh4 = g.Mesh((4,), (0, 1, 2, 3))
         shp = (8, 2048, 8192)
@@ -371,7 +416,10 @@ def main():
         gbytes = 2 * dst.numel() * 2
         others["reshard_allgather_bsm"] = {"kernel": "reshard_kernel", "what": "BSM [8,2048,8192] bf16, M split 4 ways -> whole (one shared dst buffer)",
                                            "ms": round(ms, 4), "algorithmic_bytes": gbytes, "gbs": round(gbytes / ms / 1e6, 1),
-                                           "frac_of_hbm_peak": round(gbytes / ms / 1e6 / PEAK_HBM_GBS, 3)}
+                                           "frac_of_hbm_peak": round(gbytes / ms / 1e6 / PEAK_HBM_GBS, 3),
+                                           "roofline": {"bound": "hbm", "achieved": round(gbytes / ms / 1e6, 1), "peak": PEAK_HBM_GBS,
+                                                        "unit": "GB/s", "frac": round(gbytes / ms / 1e6 / PEAK_HBM_GBS, 4),
+                                                        "algorithmic_bytes": gbytes, "kernel": "reshard_kernel"}}
         del srcs, dst
         result["others"] = others
     print(json.dumps(result), flush=True)
