@@ -11,7 +11,10 @@ w and w+4 share a SIMD) alternate, one phase apart and separated by s_barrier, b
     into 96 VGPRs, and
   * an MFMA phase: 64 v_mfma_f32_16x16x32_bf16 with no waits,
 so that each SIMD's matrix pipe always has exactly one wave issuing MFMAs (two waves issuing at once share the pipe
-badly: measured 64 % pipe efficiency with one wave starved).  16x16x32 is used rather than 32x32x16 because it moves
+badly: measured 64 % pipe efficiency with one wave starved).  Inside an MFMA phase the 4 column blocks of each row block
+are visited back and forth, so that consecutive MFMAs share one fragment operand (the chip is power-limited and operand
+switching costs: +1.4 % on the feed-forward share and +1.1 % on the experts' over restarting every row block at
+column block 0, same box; column blocks outermost with the row blocks back and forth gains 1.0 %).  16x16x32 is used rather than 32x32x16 because it moves
 half the accumulator registers per flop and the chip is power-limited: a pure MFMA loop on N(0,1) data sustains
 1996 TFLOP/s with 16x16x32 and 1700 with 32x32x16 (both reach 2480 on all-zero data).
 Global->LDS tile loads (global_load_lds_dwordx4, 1 KiB per wave-instruction) are issued only from MFMA phases, one
@@ -179,7 +182,9 @@ def mfma_phase(w, tail, nbm=8, loads=True):
     i = 0
     for q in range(2):
         for bm in range(nbm):
-            for bn in range(4):
+            # column blocks back and forth, so that from one MFMA to the next only one of the two fragment operands
+            # changes (the row block's fragment stays for four MFMAs, and at the turn the column block's stays)
+            for bn in (range(4) if (bm + q * nbm) % 2 == 0 else range(3, -1, -1)):
                 out.append(f"v_mfma_f32_16x16x32_bf16 {acc(bm, bn)}, {fb(q, bn)}, {fa(q, bm)}, {acc(bm, bn)}")
                 if i in load_pos:
                     out += load(load_pos[i])
