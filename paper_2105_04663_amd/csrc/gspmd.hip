@@ -487,7 +487,7 @@ int32_t gspmd_dot_workspace_bytes(const gspmd_mesh* mesh, const gspmd_dot_dims* 
   // A grouped call with a contracting mesh dimension keeps its partial sums either as one dense fp32 array per
   // partition or, when the problems can be joined in one launch, as one slot per output tile and partition plus a
   // counter per tile; the second layout is offered only while it stays within reach of the first.
-  if (pid < 0 && contracting && !has_scatter(mesh, cls)) {
+  if (pid < 0 && contracting) {
     const int64_t joined = joined_bytes(tiles, tiles);
     if (joined <= 2 * partial_bytes + kJoinSlack) partial_bytes = std::max(partial_bytes, joined);
   }
@@ -585,57 +585,98 @@ int32_t gspmd_grouped_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
     for (auto& kv : groups) std::sort(kv.second.begin(), kv.second.end());
   }
 
-  // One launch for the whole sum (the AllReduce of Section 4.2 folded into the contraction): when every member of a
-  // reduce group writes the same out buffer and lowers to the same output blocks, the members' problems are joined --
-  // every output tile gets one contribution per member, added in ascending mesh position by whichever workgroup
-  // finishes last.  Otherwise (a scattered sum, members with out buffers of their own, operands the MFMA kernel cannot
-  // take, a workspace sized for the dense layout only) the partials go to dense arrays and a second kernel sums them.
-  if (contracting && !has_scatter(mesh, cls) && in_dtype == GSPMD_BF16) {
+  // One launch for the whole sum (the AllReduce / ReduceScatter of Section 4.2 folded into the contraction): the
+  // problems of a reduce group's members are joined -- every output tile gets one contribution per member, added in
+  // ascending mesh position by whichever workgroup finishes last.  Two shapes qualify.  AllReduce: every member writes
+  // the same out buffer and lowers to the same output blocks.  ReduceScatter along the output's last dimension, when
+  // that is the only non-contracting rhs dimension and the scatter mesh dimension the only contracting one: each
+  // member's problems are cut into the column ranges the members own, and the pieces for one owner are joined into that
+  // owner's out shard.  Otherwise (other scattered sums, members with out buffers of their own, operands the MFMA
+  // kernel cannot take, a workspace sized for the dense layout only) the partials go to dense arrays and a second
+  // kernel sums them.
+  int n_contracting_dims = 0;
+  for (int a = 0; a < mesh->rank; ++a) n_contracting_dims += is_contracting(cls[a]) ? 1 : 0;
+  const int last_out = out_sh->rank - 1;
+  const bool scatter = has_scatter(mesh, cls);
+  const bool scatter_by_columns = scatter && n_contracting_dims == 1 && r.nrf == 1 && out_sh->dims_mapping[last_out] >= 0 &&
+                                  cls[out_sh->dims_mapping[last_out]] == GSPMD_AXIS_CONTRACTING_SCATTER;
+  if (contracting && (!scatter || scatter_by_columns) && in_dtype == GSPMD_BF16) {
     std::vector<Problem> joined;
     int32_t jlayout = 0;
     int64_t jtiles = 0, jslots = 0;
     bool ok = true;
+    const size_t out_esize = out_dtype == GSPMD_BF16 ? 2 : 4;
+    char* const dummy_c = reinterpret_cast<char*>(uintptr_t(1) << 44);      // never dereferenced: offsets are read off it
     for (auto& kv : groups) {
       const auto& members = kv.second;
+      // the members' problems: against the shared out buffer, or (scattered) against a made-up dense partial
+      std::vector<std::vector<Problem>> base(members.size());
       const gspmd_shard_buf& o0 = out_shards[members[0].second];
-      std::vector<std::vector<Problem>> pm(members.size());
       for (size_t m = 0; m < members.size() && ok; ++m) {
         const int64_t p = members[m].second;
-        ok = out_shards[p].data == o0.data && out_shards[p].row_stride == o0.row_stride;
+        if (!scatter) ok = out_shards[p].data == o0.data && out_shards[p].row_stride == o0.row_stride;
         if (!ok) break;
         int64_t e = 0;
-        if ((st = plan_partition(mesh, r, &lhs_shards[p], lhs_sh, &rhs_shards[p], rhs_sh, &out_shards[p], out_sh, p, lhs_fill, nullptr,
-                                 &pm[m], &e, &jlayout)) != GSPMD_OK) return st;
-        for (const auto& q : pm[m])
+        if ((st = plan_partition(mesh, r, &lhs_shards[p], lhs_sh, &rhs_shards[p], rhs_sh, &out_shards[p], scatter ? &part_sh : out_sh, p,
+                                 lhs_fill, scatter ? dummy_c : nullptr, &base[m], &e, &jlayout)) != GSPMD_OK) return st;
+        for (const auto& q : base[m])
           if ((q.Kv && (!q.A || !q.B)) || !q.C) return GSPMD_ERR_NULL;
-        ok = pm[m].size() == pm[0].size();
+        ok = base[m].size() == base[0].size();
       }
-      for (size_t i = 0; ok && i < pm[0].size(); ++i) {
-        std::vector<size_t> live;
-        for (size_t m = 0; m < members.size(); ++m) {
-          const Problem &q = pm[m][i], &q0 = pm[0][i];
-          ok = ok && q.C == q0.C && q.ldc == q0.ldc && q.Ms == q0.Ms && q.Ns == q0.Ns;
-          if (q.Kv > 0) {
-            if (!live.empty()) ok = ok && q.Mv == pm[live[0]][i].Mv && q.Nv == pm[live[0]][i].Nv;
-            live.push_back(m);
+      if (!ok) break;
+      // one round per owner of output columns: the one shared buffer, or every member's own slice
+      for (size_t owner = 0; ok && owner < (scatter ? members.size() : 1); ++owner) {
+        std::vector<std::vector<Problem>> pm = base;
+        if (scatter) {
+          const int64_t po = members[owner].second;
+          Bounds ob;
+          if ((st = shard_bounds(mesh, out_sh, po, &ob)) != GSPMD_OK) return st;
+          if (!out_shards[po].data && ob.shard[last_out] > 0) return GSPMD_ERR_NULL;
+          const int64_t off = ob.offset[last_out], width = ob.shard[last_out];
+          const int64_t ldo = out_sh->rank >= 2 && out_shards[po].row_stride > 0 ? out_shards[po].row_stride : width;
+          if (ldo < width || ldo > INT32_MAX || width > INT32_MAX) { ok = false; break; }
+          for (auto& list : pm)
+            for (auto& q : list) {
+              const int64_t elem = (static_cast<char*>(q.C) - dummy_c) / 4;          // offset inside the dense partial
+              if (q.Ns <= 0 || elem % q.Ns != 0) { ok = false; break; }
+              const int64_t row = elem / q.Ns;
+              const int64_t nv = std::max<int64_t>(0, std::min<int64_t>(ob.valid[last_out], static_cast<int64_t>(q.Nv) - off));
+              const int64_t b_step = (jlayout & GSPMD_LAYOUT_RHS_K_CONTIGUOUS) ? off * q.ldb : off;
+              q.B = static_cast<const char*>(q.B) + b_step * 2;
+              q.C = static_cast<char*>(out_shards[po].data) + row * ldo * static_cast<int64_t>(out_esize);
+              q.ldc = static_cast<int32_t>(ldo);
+              q.Ns = static_cast<int32_t>(width);
+              q.Nv = static_cast<int32_t>(nv);
+              if (q.Mv == 0 || q.Nv == 0 || q.Kv == 0) q.Mv = q.Nv = q.Kv = 0;
+            }
+        }
+        for (size_t i = 0; ok && i < pm[0].size(); ++i) {
+          std::vector<size_t> live;
+          for (size_t m = 0; m < members.size(); ++m) {
+            const Problem &q = pm[m][i], &q0 = pm[0][i];
+            ok = ok && q.C == q0.C && q.ldc == q0.ldc && q.Ms == q0.Ms && q.Ns == q0.Ns;
+            if (q.Kv > 0) {
+              if (!live.empty()) ok = ok && q.Mv == pm[live[0]][i].Mv && q.Nv == pm[live[0]][i].Nv;
+              live.push_back(m);
+            }
           }
+          if (!ok || live.size() > static_cast<size_t>(kMaxPartials)) { ok = false; break; }
+          if (live.size() <= 1) {
+            joined.push_back(pm[live.empty() ? 0 : live[0]][i]);       // nothing to add up (a dead problem still has its zero fill)
+            continue;
+          }
+          const int64_t t = tiles_of(pm[live[0]][i], kMfmaBM, kMfmaBN);
+          for (size_t k = 0; k < live.size(); ++k) {
+            Problem q = pm[live[k]][i];
+            q.join_count = static_cast<int32_t>(live.size());
+            q.join_slot = static_cast<int32_t>(k);
+            q.join_first = static_cast<int32_t>(jtiles);
+            joined.push_back(q);
+          }
+          jtiles += t;
+          jslots += t * static_cast<int64_t>(live.size());
+          if (jtiles > INT32_MAX) { ok = false; break; }
         }
-        if (!ok || live.size() > static_cast<size_t>(kMaxPartials)) { ok = false; break; }
-        if (live.size() <= 1) {
-          joined.push_back(pm[live.empty() ? 0 : live[0]][i]);       // nothing to add up (a dead problem still has its zero fill)
-          continue;
-        }
-        const int64_t t = tiles_of(pm[live[0]][i], kMfmaBM, kMfmaBN);
-        for (size_t k = 0; k < live.size(); ++k) {
-          Problem q = pm[live[k]][i];
-          q.join_count = static_cast<int32_t>(live.size());
-          q.join_slot = static_cast<int32_t>(k);
-          q.join_first = static_cast<int32_t>(jtiles);
-          joined.push_back(q);
-        }
-        jtiles += t;
-        jslots += t * static_cast<int64_t>(live.size());
-        if (jtiles > INT32_MAX) { ok = false; break; }
       }
       if (!ok) break;
     }
