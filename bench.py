@@ -43,6 +43,9 @@ def parse():
     ap.add_argument("--cpu-rows", type=int, default=16384, help="rows of the FFN output the CPU oracle is timed on")
     ap.add_argument("--only", default=None,
                     help="time just one of the other workloads (by name, e.g. moe_ecm_emh) and print its entry; for profiling")
+    ap.add_argument("--moe-fill", type=int, default=None,
+                    help="with --only moe_ecm_emh (or another workload with fill counts): every expert filled to this many "
+                         "rows instead of the seed-drawn counts (a diagnostic variant, not the benchmark's configuration)")
     ap.add_argument("--probe-power", action="store_true",
                     help="run only the power probe: the headline kernel looped for 4 s on the benchmark's data and on all-zero "
                          "operands, with the shader clock and package power sampled from rocm-smi (the kernel is power-limited: "
@@ -157,6 +160,10 @@ def main():
             self.lhs_sh = g.Sharding(tuple(w.lhs_shape), tuple(w.lhs_map))
             self.rhs_sh = g.Sharding(tuple(w.rhs_shape), tuple(w.rhs_map))
             self.out_sh = g.Sharding(tuple(w.out_shape), tuple(w.out_map))
+            if w.fill_range is not None and args.moe_fill is not None:
+                # the override replaces the drawn counts before the lhs is drawn, so that exactly the rows beyond it are zero
+                n_experts = w.lhs_shape[0]
+                w.draw_fill = lambda: np.full(n_experts, args.moe_fill, dtype=np.int64)
             self.fill = w.draw_fill()
             lhs_np = w.draw_lhs() if lhs_np is None else lhs_np
             rhs_np = w.draw_rhs() if rhs_np is None else rhs_np
