@@ -29,6 +29,7 @@
 #include <stdint.h>
 
 #include <mutex>
+#include <type_traits>
 
 #include "kernels_basic.h"
 #include "mainloop_asm.h"
@@ -67,6 +68,7 @@ __device__ __forceinline__ u32x4_t mask_tail8(u32x4_t v, int keep) {   // keep f
 
 // 16 bytes from an address that is only 4-byte aligned
 typedef uint32_t u32x4_align4_t __attribute__((ext_vector_type(4), aligned(4)));
+typedef __attribute__((address_space(1))) u32x4_t global_u32x4_t;
 
 // STAGED: the variant for operands whose rows are only 4-byte aligned (an even row stride that is not a multiple of
 // 8 elements, e.g. dense shards of 1250 columns): direct global->LDS loads need 16-byte aligned chunks, so every K
@@ -417,6 +419,12 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const InlineProb
   if (vec_ok && rows_16b && n0 + kMfmaBN <= P.Nv) {
     // all 256 columns valid: whole 16-byte stores, predicated by row only; bf16 through the hardware
     // round-to-nearest-even conversion
+    // Relu or not is decided once per workgroup, not per element: with the test inside the conversion loop the compiler
+    // turns every element into a compare, a select and a repack.  Stores go through global-address-space pointers
+    // (a flat store also counts as an LDS operation, and the waits for the staging reads would wait for it); all of a
+    // wave's staging reads are issued before its first store.
+    const bool relu = epilogue == GSPMD_EPILOGUE_RELU;
+    const bool whole = rows_own >= kMfmaBM;          // all 256 rows valid: no row predicates
     if constexpr (sizeof(TOut) == 2) {
       // bf16: the wave's 128 x 64 block is a 128-byte line per row, but a lane holds only 8 bytes of it per 16-column
       // block.  Stage it through the wave's own slice of LDS (free now: every wave's LDS reads are over and no tile load is in flight;
@@ -424,50 +432,74 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const InlineProb
       constexpr int kPitch = 144;
       unsigned char* slice = smem + wave * (128 * kPitch);
       typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
+      auto stage = [&](auto relu_tag) {
+        constexpr bool kRelu = decltype(relu_tag)::value;
 #pragma unroll
-      for (int bm = 0; bm < 8; ++bm)
+        for (int bm = 0; bm < 8; ++bm)
 #pragma unroll
-        for (int bn = 0; bn < 4; ++bn) {
-          float v[4];
+          for (int bn = 0; bn < 4; ++bn) {
+            float v[4];
 #pragma unroll
-          for (int j = 0; j < 4; ++j) v[j] = apply_epilogue(acc[bm][bn * 4 + j], epilogue);
-          bf16x4_t o = {static_cast<__bf16>(v[0]), static_cast<__bf16>(v[1]), static_cast<__bf16>(v[2]), static_cast<__bf16>(v[3])};
-          *reinterpret_cast<bf16x4_t*>(slice + (bm * 16 + (lane & 15)) * kPitch + bn * 32 + (lane >> 4) * 8) = o;
-        }
-      TOut* __restrict__ c0 = Cg + static_cast<int64_t>(m0 + wm * 128 + (lane >> 3)) * P.ldc + n0 + wn * 64 + (lane & 7) * 8;
+            for (int j = 0; j < 4; ++j) v[j] = apply_epilogue(acc[bm][bn * 4 + j], kRelu ? GSPMD_EPILOGUE_RELU : GSPMD_EPILOGUE_NONE);
+            bf16x4_t o = {static_cast<__bf16>(v[0]), static_cast<__bf16>(v[1]), static_cast<__bf16>(v[2]), static_cast<__bf16>(v[3])};
+            *reinterpret_cast<bf16x4_t*>(slice + (bm * 16 + (lane & 15)) * kPitch + bn * 32 + (lane >> 4) * 8) = o;
+          }
+      };
+      if (relu) stage(std::true_type{}); else stage(std::false_type{});
+      global_u32x4_t* c0 = (global_u32x4_t*)(Cg + static_cast<int64_t>(m0 + wm * 128 + (lane >> 3)) * P.ldc + n0 + wn * 64 + (lane & 7) * 8);
+      const int64_t pitch8 = static_cast<int64_t>(P.ldc);      // 8 rows of bf16 in units of 16 bytes
       const int row0 = wm * 128 + (lane >> 3);
+      u32x4_t v[16];
 #pragma unroll
-      for (int p = 0; p < 16; ++p) {
-        u32x4_t v = *reinterpret_cast<const u32x4_t*>(slice + (p * 8 + (lane >> 3)) * kPitch + (lane & 7) * 16);
-        const int row = row0 + p * 8;
-        if (row >= rows_own) v = u32x4_t{0u, 0u, 0u, 0u};
-        if (row < rows_write) *reinterpret_cast<u32x4_t*>(c0 + static_cast<int64_t>(p * 8) * P.ldc) = v;
+      for (int p = 0; p < 16; ++p) v[p] = *reinterpret_cast<const u32x4_t*>(slice + (p * 8 + (lane >> 3)) * kPitch + (lane & 7) * 16);
+      if (whole) {
+#pragma unroll
+        for (int p = 0; p < 16; ++p) c0[p * pitch8] = v[p];
+      } else {
+#pragma unroll
+        for (int p = 0; p < 16; ++p) {
+          const int row = row0 + p * 8;
+          if (row >= rows_own) v[p] = u32x4_t{0u, 0u, 0u, 0u};
+          if (row < rows_write) c0[p * pitch8] = v[p];
+        }
       }
     } else {
       // fp32: a row of the wave's block is 256 bytes, of which a lane holds 16 per 16-column block.  Staged through the
       // wave's LDS slice in two passes of 64 rows (rows padded to 272 bytes) and stored 16 lanes per row: whole rows.
       constexpr int kPitch = 272;
       unsigned char* slice = smem + wave * (128 * 144);
-      TOut* __restrict__ c0 = Cg + static_cast<int64_t>(m0 + wm * 128 + (lane >> 4)) * P.ldc + n0 + wn * 64 + (lane & 15) * 4;
+      global_u32x4_t* c0 = (global_u32x4_t*)(Cg + static_cast<int64_t>(m0 + wm * 128 + (lane >> 4)) * P.ldc + n0 + wn * 64 + (lane & 15) * 4);
+      const int64_t pitch4 = static_cast<int64_t>(P.ldc);      // 4 rows of fp32 in units of 16 bytes
 #pragma unroll
       for (int pass = 0; pass < 2; ++pass) {
+        auto stage = [&](auto relu_tag) {
+          constexpr bool kRelu = decltype(relu_tag)::value;
 #pragma unroll
-        for (int b4 = 0; b4 < 4; ++b4) {
-          const int bm = pass * 4 + b4;
+          for (int b4 = 0; b4 < 4; ++b4) {
+            const int bm = pass * 4 + b4;
 #pragma unroll
-          for (int bn = 0; bn < 4; ++bn) {
-            float4_t v;
+            for (int bn = 0; bn < 4; ++bn) {
+              float4_t v;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) v[j] = apply_epilogue(acc[bm][bn * 4 + j], epilogue);
-            *reinterpret_cast<float4_t*>(slice + (b4 * 16 + (lane & 15)) * kPitch + bn * 64 + (lane >> 4) * 16) = v;
+              for (int j = 0; j < 4; ++j) v[j] = apply_epilogue(acc[bm][bn * 4 + j], kRelu ? GSPMD_EPILOGUE_RELU : GSPMD_EPILOGUE_NONE);
+              *reinterpret_cast<float4_t*>(slice + (b4 * 16 + (lane & 15)) * kPitch + bn * 64 + (lane >> 4) * 16) = v;
+            }
           }
-        }
+        };
+        if (relu) stage(std::true_type{}); else stage(std::false_type{});
+        u32x4_t v[16];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          float4_t v = *reinterpret_cast<const float4_t*>(slice + (i * 4 + (lane >> 4)) * kPitch + (lane & 15) * 16);
-          const int row = wm * 128 + pass * 64 + i * 4 + (lane >> 4);
-          if (row >= rows_own) v = float4_t{0.f, 0.f, 0.f, 0.f};
-          if (row < rows_write) *reinterpret_cast<float4_t*>(c0 + static_cast<int64_t>(pass * 64 + i * 4) * P.ldc) = v;
+        for (int i = 0; i < 16; ++i) v[i] = *reinterpret_cast<const u32x4_t*>(slice + (i * 4 + (lane >> 4)) * kPitch + (lane & 15) * 16);
+        if (whole) {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) c0[(pass * 16 + i) * pitch4] = v[i];
+        } else {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const int row = wm * 128 + pass * 64 + i * 4 + (lane >> 4);
+            if (row >= rows_own) v[i] = u32x4_t{0u, 0u, 0u, 0u};
+            if (row < rows_write) c0[(pass * 16 + i) * pitch4] = v[i];
+          }
         }
       }
     }
