@@ -121,6 +121,10 @@ int32_t launch_problems(std::vector<Problem>& all, int32_t layout, int32_t in_dt
   const bool mfma = path != kPathFallback;
   if (join && !mfma) return GSPMD_ERR_UNSUPPORTED;              // the caller checks before it joins problems
   const int bm = mfma ? kMfmaBM : kGenTile, bn = mfma ? kMfmaBN : kGenTile;
+  // Workgroups start in tile order and the launch ends when the last one does: problems whose tiles take longest
+  // (the most K steps) go first, so that the compute units that are still busy at the end are busy with short tiles.
+  if (!join)
+    std::stable_sort(ps.begin(), ps.end(), [](const Problem& a, const Problem& b) { return a.Kv > b.Kv; });
   const int64_t tiles = assign_tiles(ps, bm, bn);
   if (tiles < 0) return GSPMD_ERR_UNSUPPORTED;
   std::vector<ZeroRect> rects;

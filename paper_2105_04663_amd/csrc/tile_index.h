@@ -22,16 +22,19 @@ GSPMD_INDEX_FN int swz_a(int row) { return (row >> 1) & 3; }
 GSPMD_INDEX_FN int swz_b(int krow) { return ((krow & 3) << 2) ^ (((krow >> 3) & 1) << 1); }
 
 // Which output tile a workgroup takes.  Workgroup b runs on XCD b % 8 (each XCD has its own L2), and 256
-// workgroups are resident at a time.  Within every window of 256 consecutive tile ids XCD x takes ids
-// [32x, 32x+32), and inside a problem ids walk bands of 8 tile rows with the row index running fastest: an
-// XCD's 32 concurrent tiles then form a block of about 8 rows x 4 columns (12 operand panels per K step instead
-// of up to 33), and a problem with few tile rows (an expert with <= 1024 occupied slots) streams every weight
-// panel exactly once, all its row tiles being in flight together.
+// workgroups are resident at a time.  Within every window of 256 consecutive tile ids (the last window may be
+// shorter) XCD x takes a run of consecutive ids -- [32x, 32x+32) of a full window, an eighth of a short one -- and
+// inside a problem ids walk bands of 8 tile rows with the row index running fastest: an XCD's 32 concurrent tiles
+// then form a block of about 8 rows x 4 columns (12 operand panels per K step instead of up to 33), and a problem
+// with few tile rows (an expert with <= 1024 occupied slots) streams every weight panel exactly once, all its row
+// tiles being in flight together.
 GSPMD_INDEX_FN int logical_tile(int b, int total) {
-  const int full = total & ~255;
-  if (b >= full) return b;
-  const int r = b & 255;
-  return (b & ~255) + (r & 7) * 32 + (r >> 3);
+  const int base = b & ~255;
+  const int left = total - base;
+  const int width = left < 256 ? left : 256;       // ids in this window
+  const int r = b - base, x = r & 7, i = r >> 3;    // XCD x, its i-th workgroup of the window
+  const int each = width >> 3, extra = width & 7;   // XCDs 0 .. extra-1 have one workgroup more
+  return base + x * each + (x < extra ? x : extra) + i;
 }
 
 constexpr int kBandRows = 8;

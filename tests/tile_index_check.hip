@@ -155,6 +155,17 @@ static void check_tile_order() {
   }
   // within a window of 256 ids, XCD x (workgroups b with b % 8 == x) takes the 32 consecutive ids [32 x, 32 x + 32)
   for (int b = 0; b < 512; ++b) CHECK((logical_tile(b, 512) & 255) / 32 == (b & 7), "XCD %d gets tile %d", b & 7, logical_tile(b, 512));
+  // a short last window is shared out the same way: the ids of one XCD are consecutive, XCD 0's first
+  for (int total : {1, 5, 8, 13, 192, 255, 256 + 192, 512 + 77}) {
+    const int base = total & ~255, width = total - base;
+    int next = base;
+    for (int x = 0; x < 8; ++x)
+      for (int b = base + x; b < total; b += 8) {
+        CHECK(logical_tile(b, total) == next, "short window: workgroup %d of %d gets tile %d, expected %d", b, total, logical_tile(b, total), next);
+        ++next;
+      }
+    CHECK(next == base + width, "short window of %d ids not covered", width);
+  }
 }
 
 int main() {
