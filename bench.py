@@ -46,6 +46,9 @@ def parse():
     ap.add_argument("--moe-fill", type=int, default=None,
                     help="with --only moe_ecm_emh (or another workload with fill counts): every expert filled to this many "
                          "rows instead of the seed-drawn counts (a diagnostic variant, not the benchmark's configuration)")
+    ap.add_argument("--tile-timeline", default=None, metavar="NAME",
+                    help="per-workgroup timeline of dot_mfma_kernel on one workload (its name, or ffn_bsm_mh for the headline): "
+                         "where a tile's time goes and how fast each XCD works; prints one JSON line")
     ap.add_argument("--probe-power", action="store_true",
                     help="run only the power probe: the headline kernel looped for 4 s on the benchmark's data and on all-zero "
                          "operands, with the shader clock and package power sampled from rocm-smi (the kernel is power-limited: "
@@ -268,6 +271,88 @@ def main():
             torch.cuda.synchronize()
             ms = e0.elapsed_time(e1) / max(n_steps[0], 1)
             out[tag] = {"ms_per_launch": round(ms, 4), "tflops": round(flops / ms / 1e9, 1), "launches": n_steps[0], "rocm_smi": load}
+        print(json.dumps(out), flush=True)
+        return
+
+    if args.tile_timeline:
+        ww = None
+        for make in (wl.ffn,) + other_makers:
+            cand = make()
+            if cand.name == args.tile_timeline:
+                ww = cand
+        if ww is None:
+            sys.stderr.write("bench.py: no workload named %r\n" % args.tile_timeline)
+            sys.exit(2)
+        st = Staged(ww)
+        for _ in range(40):
+            st.step()
+        torch.cuda.synchronize()
+        cap = 1 << 17
+        rec = torch.zeros(cap * g.TILE_TIMELINE_WORDS, dtype=torch.int64, device=dev)
+        torch.cuda.synchronize()
+        # several launches back to back, each overwriting the records of the one before: what is read back is the
+        # last one, which started on a busy GPU like the launches the benchmark times
+        g.set_tile_timeline(rec.data_ptr(), cap)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for _ in range(5):
+            st.step()
+        e0.record()
+        st.step()
+        e1.record()
+        torch.cuda.synchronize()
+        g.set_tile_timeline(0, 0)
+        d = rec.cpu().numpy().view(np.uint64).reshape(cap, g.TILE_TIMELINE_WORDS)
+        d = d[d[:, 0] != 0]
+        where = (d[:, 0] >> np.uint64(52)).astype(np.int64)
+        ts = d.copy()
+        ts[:, 0] &= np.uint64((1 << 52) - 1)
+        ts = ts.astype(np.float64) * 0.01                      # microseconds (100 MHz counter)
+        done = ts[:, 7] > 0                                    # workgroups that stored an output tile
+        t0 = ts[:, 0].min()
+
+        def seg(i, j, rows):
+            x = ts[rows, j] - ts[rows, i]
+            return {"mean": round(float(x.mean()), 2), "median": round(float(np.median(x)), 2),
+                    "p10": round(float(np.percentile(x, 10)), 2), "p90": round(float(np.percentile(x, 90)), 2)}
+        every = np.ones(len(ts), dtype=bool)
+        out = {"tile_timeline": ww.name, "unit": "us", "workgroups": int(len(ts)), "call_ms": round(e0.elapsed_time(e1), 4),
+               "first_entry_to_last_store_ms": round(float(ts[done, 7].max() - t0) / 1e3, 4),
+               "entry_to_tile_decoded": seg(0, 1, every), "decoded_to_first_loads_issued": seg(1, 2, every),
+               "loads_issued_to_k_loop_entered": seg(2, 3, every), "k_loop": seg(3, 4, every),
+               "k_loop_left_to_epilogue": seg(4, 5, done), "epilogue_stores_issued": seg(5, 6, done),
+               "stores_complete": seg(6, 7, done), "whole_workgroup": seg(0, 7, done)}
+        xcd = where >> 8
+        cu = where                                             # XCD id and compute-unit bits together name a compute unit
+        gaps, last_end = [], []
+        for c in np.unique(cu):
+            idx = np.where((cu == c) & done)[0]
+            if len(idx) == 0:
+                continue
+            o = idx[np.argsort(ts[idx, 0])]
+            gaps.extend((ts[o[1:], 0] - ts[o[:-1], 7]).tolist())
+            last_end.append(ts[o[-1], 7] - t0)
+        if gaps:
+            out["stores_complete_to_next_entry_same_cu"] = {"mean": round(float(np.mean(gaps)), 2), "median": round(float(np.median(gaps)), 2),
+                                                            "p90": round(float(np.percentile(gaps, 90)), 2)}
+        # every workgroup, also those that leave after handing in a joined contribution: from entry to the end of its K loop
+        busy = []
+        for c in np.unique(cu):
+            idx = np.where(cu == c)[0]
+            o = idx[np.argsort(ts[idx, 0])]
+            end = np.where(done[o], ts[o, 7], ts[o, 4])
+            busy.append(float((end - ts[o, 0]).sum()))
+        out["busy_per_cu_entry_to_last_stamp"] = {"min": round(min(busy), 1), "mean": round(float(np.mean(busy)), 1), "max": round(max(busy), 1)}
+        out["compute_units"] = int(len(np.unique(cu)))
+        out["last_store_per_cu"] = {"min": round(float(np.min(last_end)), 1), "mean": round(float(np.mean(last_end)), 1),
+                                    "max": round(float(np.max(last_end)), 1)}
+        out["per_xcd"] = {str(int(x)): {"workgroups": int((xcd == x).sum()),
+                                        "mean_workgroup": round(float((ts[(xcd == x) & done, 7] - ts[(xcd == x) & done, 0]).mean()), 2),
+                                        "mean_k_loop": round(float((ts[xcd == x, 4] - ts[xcd == x, 3]).mean()), 2)}
+                          for x in np.unique(xcd)}
+        order = np.argsort(ts[:, 0])
+        kl = (ts[:, 4] - ts[:, 3])[order]
+        n8 = max(len(kl) // 8, 1)
+        out["mean_k_loop_by_start_order_eighths"] = [round(float(kl[i * n8:(i + 1) * n8].mean()), 2) for i in range(8) if i * n8 < len(kl)]
         print(json.dumps(out), flush=True)
         return
 

@@ -332,6 +332,18 @@ int32_t gspmd_resharded_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
                             const int64_t* lhs_fill, int32_t epilogue,
                             void* workspace, int64_t workspace_bytes, void* hip_stream);
 
+/* Utility (no counterpart in the paper; a profiling aid for the MFMA contraction kernel).  While a record buffer is
+ * set, every later Dot launch of this process (any entry point, any stream) makes workgroup b < n_records of its
+ * MFMA kernel write record b: eight 64-bit words of the GPU's 100 MHz constant-rate counter at kernel entry (bits
+ * 52-63 hold XCD id << 8 | compute-unit id bits), tile decoded, first tile loads issued, K loop entered, K loop left,
+ * epilogue entered, stores issued, stores complete; a workgroup that leaves early (a joined contribution that is not
+ * the last to arrive) leaves words 5 to 7 untouched.  device_records: device memory of n_records * 64 bytes, 8-byte
+ * aligned, owned by the caller, who clears it and keeps it alive until the launches have finished;
+ * NULL or n_records 0 switches the timeline off (the default; the kernel then skips the stamps on one uniform branch).
+ * The setting is process-wide, not per stream: launches that overlap write to the same records.  Results of the Dot
+ * are unchanged.  Returns GSPMD_ERR_BAD_BUFFER for a misaligned pointer or a count outside [0, 2^31). */
+int32_t gspmd_set_tile_timeline(void* device_records, int64_t n_records);
+
 #ifdef __cplusplus
 }
 #endif

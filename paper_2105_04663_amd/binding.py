@@ -17,8 +17,9 @@ EXPORTED_SYMBOLS = (
     "gspmd_local_dot", "gspmd_grouped_dot", "gspmd_reduce_partials", "gspmd_shard_extract",
     "gspmd_shard_assemble", "gspmd_plan_dot", "gspmd_infer_out_sharding", "gspmd_reshard_workspace_bytes", "gspmd_reshard",
     "gspmd_compatible_operand_shardings", "gspmd_resharded_dot_workspace_bytes", "gspmd_resharded_dot",
-    "gspmd_grouped_dot_noalloc",
+    "gspmd_grouped_dot_noalloc", "gspmd_set_tile_timeline",
 )
+TILE_TIMELINE_WORDS = 8
 NOALLOC_MAX_WORKSPACE_BYTES = 32 * 1024 * 1024
 
 
@@ -90,6 +91,7 @@ def load_library():
     lib.gspmd_resharded_dot.argtypes = [pm, pd, pb, ps, pb, ps, pb, ps, pi64, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p]
     lib.gspmd_plan_dot.argtypes = [pm, pd, ps, ps, ps, C.c_int64, C.c_int64, C.c_int64, C.c_int64, pi64,
                                    C.POINTER(_CGemmDesc), C.c_int64, pi64]
+    lib.gspmd_set_tile_timeline.argtypes = [C.c_void_p, C.c_int64]
     for name in EXPORTED_SYMBOLS[1:]:
         getattr(lib, name).restype = C.c_int32
     _LIB = lib
@@ -344,3 +346,8 @@ def shard_assemble(mesh: Mesh, sharding: Sharding, partition_id: int, shard: Sha
     m, s, b = mesh._c(), sharding._c(), shard._c()
     _check(load_library().gspmd_shard_assemble(C.byref(m), C.byref(s), int(partition_id), C.byref(b),
                                                C.c_void_p(global_data), C.c_void_p(stream)), "gspmd_shard_assemble")
+
+
+def set_tile_timeline(device_records: int, n_records: int) -> None:
+    """gspmd_set_tile_timeline: device_records = address of n_records * 64 bytes of cleared device memory, or 0 to switch off."""
+    _check(load_library().gspmd_set_tile_timeline(C.c_void_p(int(device_records) or None), int(n_records)), "gspmd_set_tile_timeline")

@@ -2,6 +2,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cstring>
 #include <map>
 #include <vector>
@@ -92,6 +93,10 @@ bool mfma_eligible(const std::vector<Problem>& ps, int32_t in_dtype, int32_t lay
 // placed in order), and cost no workgroup launches.  Tables of up to kInlineProblems problems and kInlineRects
 // rectangles travel as kernel arguments; larger ones are uploaded into the workspace with a stream-ordered copy from
 // a temporary host buffer (HIP stages a pageable source before the call returns).
+// Where the MFMA kernel writes its per-workgroup timeline while gspmd_set_tile_timeline has one set (a profiling aid).
+std::atomic<unsigned long long*> g_timeline{nullptr};
+std::atomic<int> g_timeline_records{0};
+
 // Workspace of a launch with joined problems: one arrival counter and join_count slots of kJoinSlotBytes per joined
 // output tile.
 constexpr int64_t kJoinSlotBytes = static_cast<int64_t>(kMfmaBM) * kMfmaBN * 4;
@@ -169,7 +174,8 @@ int32_t launch_problems(std::vector<Problem>& all, int32_t layout, int32_t in_dt
         if (hipGetLastError() != hipSuccess) return GSPMD_ERR_DEVICE;
       }
       if (!launch_dot_mfma(inl, tab, n, static_cast<int>(tiles), layout, out_dtype, path == kPathMfmaStaged, epilogue, join ? join->partials : nullptr,
-                           join ? join->counters : nullptr, stream)) return GSPMD_ERR_DEVICE;
+                           join ? join->counters : nullptr, g_timeline.load(std::memory_order_acquire),
+                           g_timeline_records.load(std::memory_order_acquire), stream)) return GSPMD_ERR_DEVICE;
     } else {
       const dim3 grid(static_cast<unsigned>(tiles)), block(256);
       if (in_dtype == GSPMD_F32)
@@ -1145,5 +1151,20 @@ int32_t gspmd_resharded_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
   const int64_t left = workspace_bytes - (ws - static_cast<char*>(workspace));
   return gspmd_grouped_dot(mesh, dims, luse, &l2, ruse, &r2, out_shards, out_sh, lhs_fill, epilogue, ws, left, hip_stream);
 } catch (...) { return GSPMD_ERR_HOST_MEMORY; }
+
+int32_t gspmd_set_tile_timeline(void* device_records, int64_t n_records) try {
+  if (n_records < 0 || n_records > INT32_MAX) return GSPMD_ERR_BAD_BUFFER;
+  if (device_records == nullptr || n_records == 0) {
+    g_timeline.store(nullptr, std::memory_order_release);
+    g_timeline_records.store(0, std::memory_order_release);
+    return GSPMD_OK;
+  }
+  if (reinterpret_cast<uintptr_t>(device_records) & 7) return GSPMD_ERR_BAD_BUFFER;
+  g_timeline_records.store(static_cast<int>(n_records), std::memory_order_release);
+  g_timeline.store(static_cast<unsigned long long*>(device_records), std::memory_order_release);
+  return GSPMD_OK;
+} catch (...) {
+  return GSPMD_ERR_HOST_MEMORY;
+}
 
 }  // extern "C"

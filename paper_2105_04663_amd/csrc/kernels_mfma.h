@@ -70,6 +70,19 @@ __device__ __forceinline__ u32x4_t mask_tail8(u32x4_t v, int keep) {   // keep f
 typedef uint32_t u32x4_align4_t __attribute__((ext_vector_type(4), aligned(4)));
 typedef __attribute__((address_space(1))) u32x4_t global_u32x4_t;
 
+// Profiling aid (gspmd_set_tile_timeline): one record of eight 64-bit words per workgroup, written by its thread 0.
+// Words 0-7 hold the 100 MHz constant-rate counter at: kernel entry (bits 52-63: XCD id << 8 | compute-unit bits
+// 8-15 of the hardware id register), tile decoded, first tile loads issued, first tiles landed (K loop starts), K
+// loop left, epilogue starts (leftover K and joined sums done), stores issued, stores complete.  `rec` is null
+// when the timeline is off; the branch is uniform and costs two scalar instructions per stamp.
+constexpr int kTimelineWords = 8;
+__device__ __forceinline__ void timeline_stamp(unsigned long long* rec, int word, int t, unsigned long long tag = 0) {
+  if (rec == nullptr) return;
+  unsigned long long now;
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_memrealtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(now) :: "memory");
+  if (t == 0) rec[word] = now | (tag << 52);
+}
+
 // STAGED: the variant for operands whose rows are only 4-byte aligned (an even row stride that is not a multiple of
 // 8 elements, e.g. dense shards of 1250 columns): direct global->LDS loads need 16-byte aligned chunks, so every K
 // tile goes through registers instead -- the path the other variant uses for what is left of K after its assembly
@@ -77,17 +90,25 @@ typedef __attribute__((address_space(1))) u32x4_t global_u32x4_t;
 // valid are loaded 4 bytes at a time, so that no read leaves the rows' valid part by more than one element.
 template <typename TOut, int LAYOUT, bool STAGED>
 __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const InlineProblems inl, const Problem* __restrict__ tab, int n_prob, int epilogue,
-                                                                float* __restrict__ join_partials, uint32_t* __restrict__ join_counters) {
+                                                                float* __restrict__ join_partials, uint32_t* __restrict__ join_counters,
+                                                                unsigned long long* __restrict__ timeline, int timeline_records) {
   constexpr bool AKM = (LAYOUT & GSPMD_LAYOUT_LHS_K_MAJOR) != 0, BKC = (LAYOUT & GSPMD_LAYOUT_RHS_K_CONTIGUOUS) != 0;
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   const int t = threadIdx.x, lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
   const int wm = wave >> 2, wn = wave & 3;     // wm is also the ping-pong group
 
+  unsigned long long* const rec = (timeline != nullptr && static_cast<int>(blockIdx.x) < timeline_records)
+                                      ? timeline + static_cast<size_t>(blockIdx.x) * kTimelineWords : nullptr;
+  if (rec != nullptr) {
+    const unsigned where = ((__builtin_amdgcn_s_getreg((31 << 11) | 20) & 15u) << 8) | ((__builtin_amdgcn_s_getreg((31 << 11) | 4) >> 8) & 255u);
+    timeline_stamp(rec, 0, t, where);
+  }
   const int tile = logical_tile(blockIdx.x, gridDim.x);
   const Problem P = lookup_problem(tab, n_prob, tile);
+  const int local = tile - P.tile_begin;            // which of its problem's output tiles this workgroup computes
   int tile_row, n0;
-  tile_origin(tile - P.tile_begin, P.Mv, P.tiles_n, &tile_row, &n0);
+  tile_origin(local, P.Mv, P.tiles_n, &tile_row, &n0);
   // rows [m0, m_end) are this tile's own (valid rows are split evenly over the tile rows, in 16-row blocks); the last
   // tile row also writes the zeros that follow the valid rows, up to the end of its 256-row footprint
   const TileRows own = tile_rows(tile_row, P.Mv);
@@ -256,12 +277,15 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const InlineProb
         __syncthreads();
       }
     } else {
+    timeline_stamp(rec, 1, t);
     if (nk64 > 0) {
       // ---- prologue: group 0 loads tiles 0 and 2, group 1 tiles 1 and 3; tiles 0 and 1 must have landed
       load_tile(wm);
       load_tile(wm + 2);
+      timeline_stamp(rec, 2, t);
       __builtin_amdgcn_s_waitcnt(waitcnt_imm(8, 0));
       __builtin_amdgcn_s_barrier();
+      timeline_stamp(rec, 3, t);
       {   // ---- K loop over the full 64-wide steps: hand-scheduled assembly, see gen_mainloop.py for the register plan
         // a K-contiguous operand is read from the part that holds this wave's rows: half wm of the lhs, wn >> 1 of the rhs
         const uint32_t ard = lds0 + (AKM ? a_frag : kc_half_frag_offset(0, lane));
@@ -322,6 +346,7 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const InlineProb
     // ---- what is left of K (< 64): up to two tiles, the last one possibly partial.  Group 0 fetches the first and
     // group 1 the second as soon as they leave the loop (group 0 a phase earlier), both in flight together; they go
     // through registers (zeroed beyond the valid K) into stages 0 and 1 once every load of the loop has landed.
+    timeline_stamp(rec, 4, t);
     const int ntail = (P.Kv - nkt * kMfmaBK + kMfmaBK - 1) / kMfmaBK;
     {
       u32x4_t ta[4], tb[4];
@@ -362,7 +387,7 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const InlineProb
   if (P.join_count > 1) {
     constexpr int kDeviceScope = 16;                       // sc1
     const int S = P.join_count;
-    const int64_t jt = static_cast<int64_t>(P.join_first) + (tile - P.tile_begin);
+    const int64_t jt = static_cast<int64_t>(P.join_first) + local;
     const __amdgpu_buffer_rsrc_t slots = __builtin_amdgcn_make_buffer_rsrc(join_partials + ((jt * S) << 16), 0, S << 18, 0x00020000);
     const int at = (wave * 2048 + lane) * 16;              // this lane's place inside a slot; quad q at + q KiB
 #pragma unroll
@@ -370,7 +395,7 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const InlineProb
 #pragma unroll
       for (int bn = 0; bn < 4; ++bn) {
         const float4_t v = {acc[bm][4 * bn], acc[bm][4 * bn + 1], acc[bm][4 * bn + 2], acc[bm][4 * bn + 3]};
-        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, v), slots, at + (bm * 4 + bn) * 1024, P.join_slot << 18, kDeviceScope);
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, v), slots, at, (P.join_slot << 18) + (bm * 4 + bn) * 1024, kDeviceScope);
       }
     GSPMD_WAIT_ALL();                                      // this wave's stores have reached memory
     __syncthreads();                                       // ... and so have the other seven waves'
@@ -378,38 +403,80 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const InlineProb
     if (t == 0) *flag = __hip_atomic_fetch_add(join_counters + jt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     const uint32_t before = *flag;
-    if (before != static_cast<uint32_t>(S - 1)) return;
-    // A quarter of the accumulators (8 quads) at a time, three slots (96 spare registers) in flight together, added
-    // in slot order: two round trips to memory per quarter for up to six contributions.
+    if (before != static_cast<uint32_t>(S - 1)) {
+      if (rec != nullptr && t == 0) rec[5] = rec[6] = rec[7] = 0;      // not this launch's last arriver at the tile
+      return;
+    }
+    // The sum over the slots in ascending order.  This workgroup's own contribution is still in its accumulators, so
+    // only the other S - 1 slots are read back: a quarter of the accumulators (8 quads) at a time, up to three slots
+    // (96 spare registers) in flight together -- one round trip to memory per quarter for up to four contributions.
+    // Until the own slot's turn comes, the sum of the slots before it is kept in the registers of the first slot
+    // loaded (`head`); then head + own continues in the accumulators.  Same additions, same order, same operands as
+    // adding up all S slots one after the other.
+    const int mine = P.join_slot, others = S - 1;
 #pragma unroll
     for (int qt = 0; qt < 4; ++qt) {
-      for (int sl0 = 0; sl0 < S; sl0 += 3) {
-        u32x4_t in[3][8];
+      u32x4_t in[3][8];
+      bool folded = mine == 0;                    // the accumulators already hold the running sum
+      auto fetch = [&](int d, int other) {        // slot number of the other-th of the other slots
+        const int sl = other < mine ? other : other + 1;
 #pragma unroll
-        for (int d = 0; d < 3; ++d)
-          if (sl0 + d < S) {
+        for (int i = 0; i < 8; ++i)
+          in[d][i] = __builtin_amdgcn_raw_buffer_load_b128(slots, at, (sl << 18) + (qt * 8 + i) * 1024, kDeviceScope);   // the quad's place goes into the scalar offset: one address register for all loads
+      };
+      auto fold_head = [&]() {                    // head + own
 #pragma unroll
-            for (int i = 0; i < 8; ++i)
-              in[d][i] = __builtin_amdgcn_raw_buffer_load_b128(slots, at + (qt * 8 + i) * 1024, (sl0 + d) << 18, kDeviceScope);
+        for (int i = 0; i < 8; ++i) {
+          const float4_t h = __builtin_bit_cast(float4_t, in[0][i]);
+          const int bm = qt * 2 + (i >> 2), bn = i & 3;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) acc[bm][4 * bn + r] = h[r] + acc[bm][4 * bn + r];
+        }
+        folded = true;
+      };
+      auto take = [&](int d, int other) {
+        const int sl = other < mine ? other : other + 1;
+        if (!folded && sl > mine) fold_head();
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const float4_t v = __builtin_bit_cast(float4_t, in[d][i]);
+          const int bm = qt * 2 + (i >> 2), bn = i & 3;
+          if (folded) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[bm][4 * bn + r] = acc[bm][4 * bn + r] + v[r];
+          } else if (d != 0) {
+            float4_t h = __builtin_bit_cast(float4_t, in[0][i]);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) h[r] = h[r] + v[r];
+            in[0][i] = __builtin_bit_cast(u32x4_t, h);
           }
+        }
+      };
+      // first round trip: up to three of the others; later ones: two at a time beside the head
+#pragma unroll
+      for (int d = 0; d < 3; ++d)
+        if (d < others) fetch(d, d);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int d = 0; d < 3; ++d)
+        if (d < others) take(d, d);
+      __builtin_amdgcn_sched_barrier(0);
+      for (int k = 3; k < others; k += 2) {
+#pragma unroll
+        for (int d = 0; d < 2; ++d)
+          if (k + d < others) fetch(1 + d, k + d);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int d = 0; d < 3; ++d)
-          if (sl0 + d < S) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-              const float4_t v = __builtin_bit_cast(float4_t, in[d][i]);
-              const int bm = qt * 2 + (i >> 2), bn = i & 3;
-#pragma unroll
-              for (int r = 0; r < 4; ++r) acc[bm][4 * bn + r] = (sl0 + d == 0) ? v[r] : acc[bm][4 * bn + r] + v[r];
-            }
-          }
+        for (int d = 0; d < 2; ++d)
+          if (k + d < others) take(1 + d, k + d);
         __builtin_amdgcn_sched_barrier(0);
       }
+      if (!folded) fold_head();                   // the own slot is the last one
     }
     __syncthreads();     // the flag's word is about to be reused as staging
   }
 
+  timeline_stamp(rec, 5, t);
   // ---- epilogue: lane holds, for row m, columns n .. n+3 of each 16-column block
   TOut* __restrict__ Cg = static_cast<TOut*>(P.C);
   const bool vec_ok = ((P.ldc & 3) == 0) && ((reinterpret_cast<uintptr_t>(Cg) & 15) == 0);
@@ -503,6 +570,11 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const InlineProb
         }
       }
     }
+    if (rec != nullptr) {
+      timeline_stamp(rec, 6, t);
+      GSPMD_WAIT_ALL();
+      timeline_stamp(rec, 7, t);
+    }
     return;
   }
 #pragma unroll
@@ -533,6 +605,11 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const InlineProb
       }
     }
   }
+  if (rec != nullptr) {
+    timeline_stamp(rec, 6, t);
+    GSPMD_WAIT_ALL();
+    timeline_stamp(rec, 7, t);
+  }
 }
 
 constexpr int kMaxDevices = 64;
@@ -541,7 +618,7 @@ constexpr int kMaxDevices = 64;
 // from several host threads.
 template <typename TOut, int LAYOUT, bool STAGED>
 inline bool launch_dot_mfma_as(const InlineProblems& inl, const Problem* tab, int n_prob, int tiles, int epilogue, float* join_partials,
-                               uint32_t* join_counters, hipStream_t stream) {
+                               uint32_t* join_counters, unsigned long long* timeline, int timeline_records, hipStream_t stream) {
   static std::once_flag once[kMaxDevices];
   static bool ok[kMaxDevices];
   int dev = 0;
@@ -552,30 +629,33 @@ inline bool launch_dot_mfma_as(const InlineProblems& inl, const Problem* tab, in
   });
   if (!ok[dev]) return false;
   const dim3 grid(static_cast<unsigned>(tiles)), block(kMfmaThreads);
-  hipLaunchKernelGGL((dot_mfma_kernel<TOut, LAYOUT, STAGED>), grid, block, kMfmaLds, stream, inl, tab, n_prob, epilogue, join_partials, join_counters);
+  hipLaunchKernelGGL((dot_mfma_kernel<TOut, LAYOUT, STAGED>), grid, block, kMfmaLds, stream, inl, tab, n_prob, epilogue, join_partials, join_counters,
+                     timeline, timeline_records);
   return hipGetLastError() == hipSuccess;
 }
 
 template <typename TOut, bool STAGED>
 inline bool launch_dot_mfma_layout(const InlineProblems& inl, const Problem* tab, int n_prob, int tiles, int32_t layout, int epilogue,
-                                   float* join_partials, uint32_t* join_counters, hipStream_t stream) {
+                                   float* join_partials, uint32_t* join_counters, unsigned long long* timeline, int timeline_records,
+                                   hipStream_t stream) {
   switch (layout & 3) {
-    case 0: return launch_dot_mfma_as<TOut, 0, STAGED>(inl, tab, n_prob, tiles, epilogue, join_partials, join_counters, stream);
-    case 1: return launch_dot_mfma_as<TOut, 1, STAGED>(inl, tab, n_prob, tiles, epilogue, join_partials, join_counters, stream);
-    case 2: return launch_dot_mfma_as<TOut, 2, STAGED>(inl, tab, n_prob, tiles, epilogue, join_partials, join_counters, stream);
-    default: return launch_dot_mfma_as<TOut, 3, STAGED>(inl, tab, n_prob, tiles, epilogue, join_partials, join_counters, stream);
+    case 0: return launch_dot_mfma_as<TOut, 0, STAGED>(inl, tab, n_prob, tiles, epilogue, join_partials, join_counters, timeline, timeline_records, stream);
+    case 1: return launch_dot_mfma_as<TOut, 1, STAGED>(inl, tab, n_prob, tiles, epilogue, join_partials, join_counters, timeline, timeline_records, stream);
+    case 2: return launch_dot_mfma_as<TOut, 2, STAGED>(inl, tab, n_prob, tiles, epilogue, join_partials, join_counters, timeline, timeline_records, stream);
+    default: return launch_dot_mfma_as<TOut, 3, STAGED>(inl, tab, n_prob, tiles, epilogue, join_partials, join_counters, timeline, timeline_records, stream);
   }
 }
 
 // `staged`: the operands allow 4-byte but not 16-byte aligned chunk loads
 inline bool launch_dot_mfma(const InlineProblems& inl, const Problem* tab, int n_prob, int tiles, int32_t layout, int32_t out_dtype,
-                            bool staged, int epilogue, float* join_partials, uint32_t* join_counters, hipStream_t stream) {
+                            bool staged, int epilogue, float* join_partials, uint32_t* join_counters, unsigned long long* timeline,
+                            int timeline_records, hipStream_t stream) {
   const bool f32 = out_dtype == GSPMD_F32;
   if (staged)
-    return f32 ? launch_dot_mfma_layout<float, true>(inl, tab, n_prob, tiles, layout, epilogue, join_partials, join_counters, stream)
-               : launch_dot_mfma_layout<bf16_bits, true>(inl, tab, n_prob, tiles, layout, epilogue, join_partials, join_counters, stream);
-  return f32 ? launch_dot_mfma_layout<float, false>(inl, tab, n_prob, tiles, layout, epilogue, join_partials, join_counters, stream)
-             : launch_dot_mfma_layout<bf16_bits, false>(inl, tab, n_prob, tiles, layout, epilogue, join_partials, join_counters, stream);
+    return f32 ? launch_dot_mfma_layout<float, true>(inl, tab, n_prob, tiles, layout, epilogue, join_partials, join_counters, timeline, timeline_records, stream)
+               : launch_dot_mfma_layout<bf16_bits, true>(inl, tab, n_prob, tiles, layout, epilogue, join_partials, join_counters, timeline, timeline_records, stream);
+  return f32 ? launch_dot_mfma_layout<float, false>(inl, tab, n_prob, tiles, layout, epilogue, join_partials, join_counters, timeline, timeline_records, stream)
+             : launch_dot_mfma_layout<bf16_bits, false>(inl, tab, n_prob, tiles, layout, epilogue, join_partials, join_counters, timeline, timeline_records, stream);
 }
 
 }  // namespace gspmd
