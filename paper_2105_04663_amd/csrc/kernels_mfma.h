@@ -83,6 +83,32 @@ __device__ __forceinline__ void timeline_stamp(unsigned long long* rec, int word
   if (t == 0) rec[word] = now | (tag << 52);
 }
 
+// Zeros over rows [row_begin, row_end) x columns [col_begin, col_end) of an output block, by all kMfmaThreads threads of
+// the workgroup: the rows of the static block below the last tile row's footprint.  `vec`: 16-byte stores are
+// aligned (checked by the caller for the block's pointer, row stride and col_begin) and the width is a multiple of them.
+template <typename TOut>
+__device__ __forceinline__ void zero_rows_below(TOut* __restrict__ C, int ldc, int row_begin, int row_end, int col_begin, int col_end,
+                                                bool vec, int t) {
+  const int width = col_end - col_begin;
+  if (row_end <= row_begin || width <= 0) return;
+  if (vec) {
+    constexpr int kPer = 16 / static_cast<int>(sizeof(TOut));          // elements per store
+    const int per_row = width / kPer;                                  // stores per row
+    const int total = (row_end - row_begin) * per_row;
+    const u32x4_t z = {0u, 0u, 0u, 0u};
+    for (int i = t; i < total; i += kMfmaThreads) {
+      const int r = i / per_row, c = (i - r * per_row) * kPer;
+      *(global_u32x4_t*)(C + static_cast<int64_t>(row_begin + r) * ldc + col_begin + c) = z;
+    }
+  } else {
+    const int total = (row_end - row_begin) * width;
+    for (int i = t; i < total; i += kMfmaThreads) {
+      const int r = i / width, c = i - r * width;
+      store_from_float<TOut>(C + static_cast<int64_t>(row_begin + r) * ldc + col_begin + c, 0.f);
+    }
+  }
+}
+
 // STAGED: the variant for operands whose rows are only 4-byte aligned (an even row stride that is not a multiple of
 // 8 elements, e.g. dense shards of 1250 columns): direct global->LDS loads need 16-byte aligned chunks, so every K
 // tile goes through registers instead -- the path the other variant uses for what is left of K after its assembly
@@ -483,6 +509,13 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const InlineProb
   // the whole-tile path stores 16 bytes per lane: rows of 8 bf16 or 4 fp32 elements must keep that alignment
   const bool rows_16b = (P.ldc & (16 / static_cast<int>(sizeof(TOut)) - 1)) == 0;
   const int rows_own = m_end - m0, rows_write = m_write_end - m0;    // of the tile's 256 rows: valid, written (zeros between)
+  // the last tile row of a problem also clears what the static block has below its 256-row footprint (an expert with
+  // few occupied slots), over this tile's columns; the static columns right of the last tile column are cleared apart
+  if (m_end == P.Mv && m_write_end < P.Ms) {
+    const int col_end = min(n0 + kMfmaBN, P.Ns);
+    constexpr int kPer = 16 / static_cast<int>(sizeof(TOut));
+    zero_rows_below<TOut>(Cg, P.ldc, m_write_end, P.Ms, n0, col_end, vec_ok && rows_16b && ((col_end - n0) % kPer) == 0, t);
+  }
   if (vec_ok && rows_16b && n0 + kMfmaBN <= P.Nv) {
     // all 256 columns valid: whole 16-byte stores, predicated by row only; bf16 through the hardware
     // round-to-nearest-even conversion
