@@ -135,13 +135,13 @@ int32_t launch_problems(std::vector<Problem>& all, int32_t layout, int32_t in_dt
   std::vector<ZeroRect> rects;
   for (const auto& p : all) {
     if (p.join_slot > 0) continue;                              // one of the joined problems speaks for their common output
-    const int32_t rows_done = mfma ? rows_written(p.Mv, p.Ms)
+    // rows that the contraction kernel's tiles write or clear; the MFMA kernel's last tile row also clears up to
+    // kRowsBelow rows below its footprint
+    const int32_t rows_done = mfma ? rows_cleared(p.Mv, p.Ms)
                                    : static_cast<int32_t>(std::min<int64_t>(p.Ms, (static_cast<int64_t>(p.Mv) + bm - 1) / bm * bm));
     const int32_t cols_done = static_cast<int32_t>(std::min<int64_t>(p.Ns, (static_cast<int64_t>(p.Nv) + bn - 1) / bn * bn));
-    // the MFMA kernel's last tile row clears the rows below it over its own columns; the scalar kernel does not
-    const bool rows_by_kernel = mfma && rows_done > 0;
-    if (rows_done < p.Ms && !rows_by_kernel) rects.push_back(ZeroRect{p.C, p.ldc, rows_done, p.Ms, 0, p.Ns, 0});
-    if (cols_done < p.Ns && rows_done > 0) rects.push_back(ZeroRect{p.C, p.ldc, 0, rows_by_kernel ? p.Ms : rows_done, cols_done, p.Ns, 0});
+    if (rows_done < p.Ms) rects.push_back(ZeroRect{p.C, p.ldc, rows_done, p.Ms, 0, p.Ns, 0});
+    if (cols_done < p.Ns && rows_done > 0) rects.push_back(ZeroRect{p.C, p.ldc, 0, rows_done, cols_done, p.Ns, 0});
   }
   const bool inline_tables = ps.size() <= static_cast<size_t>(kInlineProblems) && rects.size() <= static_cast<size_t>(kInlineRects);
   const int64_t prob_bytes = static_cast<int64_t>(ps.size()) * sizeof(Problem);

@@ -510,11 +510,12 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const InlineProb
   const bool rows_16b = (P.ldc & (16 / static_cast<int>(sizeof(TOut)) - 1)) == 0;
   const int rows_own = m_end - m0, rows_write = m_write_end - m0;    // of the tile's 256 rows: valid, written (zeros between)
   // the last tile row of a problem also clears what the static block has below its 256-row footprint (an expert with
-  // few occupied slots), over this tile's columns; the static columns right of the last tile column are cleared apart
+  // few occupied slots; at most kRowsBelow rows), over this tile's columns; what lies beyond, and the static columns
+  // right of the last tile column, are cleared by the fill kernel
   if (m_end == P.Mv && m_write_end < P.Ms) {
     const int col_end = min(n0 + kMfmaBN, P.Ns);
     constexpr int kPer = 16 / static_cast<int>(sizeof(TOut));
-    zero_rows_below<TOut>(Cg, P.ldc, m_write_end, P.Ms, n0, col_end, vec_ok && rows_16b && ((col_end - n0) % kPer) == 0, t);
+    zero_rows_below<TOut>(Cg, P.ldc, m_write_end, rows_cleared(P.Mv, P.Ms), n0, col_end, vec_ok && rows_16b && ((col_end - n0) % kPer) == 0, t);
   }
   if (vec_ok && rows_16b && n0 + kMfmaBN <= P.Nv) {
     // all 256 columns valid: whole 16-byte stores, predicated by row only; bf16 through the hardware

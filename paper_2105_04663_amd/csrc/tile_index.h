@@ -122,6 +122,16 @@ GSPMD_INDEX_FN int rows_written(int rows_valid, int rows_static) {
   return end < rows_static ? end : rows_static;
 }
 
+// Rows of the static output block that the workgroups of a problem's last tile row clear in all: their own footprint
+// and up to kRowsBelow rows below it (an expert with few occupied slots).  A block that goes on beyond that is
+// cleared by the fill kernel, which spreads the work over the whole chip.
+constexpr int kRowsBelow = 1024;
+GSPMD_INDEX_FN int rows_cleared(int rows_valid, int rows_static) {
+  const int written = rows_written(rows_valid, rows_static);
+  if (written <= 0) return 0;
+  return rows_static - written <= kRowsBelow ? rows_static : written + kRowsBelow;
+}
+
 // Tile `local` (0-based inside its problem) of a problem with `rows_valid` valid rows and `tiles_n` tile columns: its
 // tile row and its first column.  Ids walk bands of kBandRows tile rows, the row index running fastest inside a band.
 GSPMD_INDEX_FN void tile_origin(int local, int rows_valid, int tiles_n, int* tile_row, int* n0) {

@@ -235,6 +235,30 @@ def test_fill_counts_that_end_in_every_row_block_of_a_tile():
         assert not got[e, fills[e]:].any()
 
 
+@pytest.mark.parametrize("out_dtype", ["f32", "bf16"])
+def test_static_rows_far_below_the_last_tile_row_are_cleared(out_dtype):
+    # Capacity 2700 with experts filled to 1, 300, 1400, 2700 and 0 slots: the last tile row's workgroups clear up to
+    # 1024 rows below their footprint, the fill kernel the rest (and the whole block of the empty expert); 261 columns
+    # leave a last tile column of 5, which takes the element-wise stores.  Outputs start as NaN.
+    fills = [1, 300, 1400, 2700, 0]
+    E, C, M, H = len(fills), 2700, 136, 261
+    w = wl.moe(E=E, C=C, M=M, H=H)
+    fill = np.array(fills, dtype=np.int64)
+    lhs, rhs = wl.draw_small_int_bf16(21, w.lhs_shape), wl.draw_small_int_bf16(22, w.rhs_shape)
+    for e in range(E):
+        lhs[e, fills[e]:] = 0x7FC0
+    st = Staged(w, lhs, rhs, row_align=8, out_dtype=out_dtype)
+    st.run_grouped(fill=fill)
+    ref = od.dot_general(od.apply_fill(widen(w, lhs), (0,), 1, fill), widen(w, rhs), w.lhs_batch, w.rhs_batch, w.lhs_contract, w.rhs_contract)
+    got = st.out_shard(0)
+    for e in range(E):
+        want = ref[e] if out_dtype == "f32" else torch.from_numpy(ref[e]).to(torch.bfloat16).double().numpy()
+        assert np.array_equal(got[e], want), f"fill {fills[e]}"      # integer sums: exact in fp32, one rounding to bf16
+        assert not got[e, fills[e]:].any()
+    raw = st.out[0][1].float().cpu().numpy()
+    assert not np.isnan(raw.reshape(E * C, -1)[:, :H]).any()
+
+
 @pytest.mark.parametrize("mode", ["local", "grouped"])
 def test_moe_weight_gradient_fill_limits_the_contraction(mode):
     # ECM,ECH->EMH: the capacity slots contract; slots beyond the fill count hold garbage (NaN) in BOTH operands here

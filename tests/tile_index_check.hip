@@ -155,6 +155,14 @@ static void check_tile_order() {
   }
   // within a window of 256 ids, XCD x (workgroups b with b % 8 == x) takes the 32 consecutive ids [32 x, 32 x + 32)
   for (int b = 0; b < 512; ++b) CHECK((logical_tile(b, 512) & 255) / 32 == (b & 7), "XCD %d gets tile %d", b & 7, logical_tile(b, 512));
+  // rows cleared by a problem's tiles: never less than what they write, never more than 1024 rows below it, all of a
+  // block that ends within those rows
+  for (int valid : {0, 1, 255, 256, 257, 745, 1000, 5000})
+    for (int extra : {0, 1, 23, 1024, 1025, 4000}) {
+      const int stat = valid + extra, w = rows_written(valid, stat), c = rows_cleared(valid, stat);
+      CHECK(c >= w && c <= stat && c - w <= kRowsBelow, "rows_cleared(%d, %d) = %d, written %d", valid, stat, c, w);
+      CHECK(valid == 0 ? c == 0 : (stat - w <= kRowsBelow ? c == stat : c == w + kRowsBelow), "rows_cleared(%d, %d) = %d", valid, stat, c);
+    }
   // a short last window is shared out the same way: the ids of one XCD are consecutive, XCD 0's first
   for (int total : {1, 5, 8, 13, 192, 255, 256 + 192, 512 + 77}) {
     const int base = total & ~255, width = total - base;
