@@ -235,6 +235,8 @@ def main():
         fl = ww.useful_flops(s2.fill)
         entry = {"ms_per_step": round(wall, 4), "tflops": round(fl / (wall * 1e-3) / 1e12, 2),
                  "pct_of_peak": round(100.0 * fl / (wall * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 2), "useful_flops": fl,
+                 # the other convention: static shard shapes and all capacity slots counted as work
+                 "padded_flops": ww.padded_flops(),
                  "einsum": ww.einsum, "partitions": ww.n_partitions,
                  # the step's device time between two events on the launch stream: the contraction kernel plus, where the
                  # workload has them, the zero fill and the sum of partials
@@ -396,7 +398,7 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall_ms, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "ffn_bsm_mh: BSM,MH->BSH B=8 S=2048 M=8192 H_local=8192 (one device's share of a 2D mesh)",
-                   "einsum": w.einsum, "useful_flops": flops, "entry_point": "gspmd_grouped_dot"},
+                   "einsum": w.einsum, "useful_flops": flops, "padded_flops": w.padded_flops(), "entry_point": "gspmd_grouped_dot"},
         "pct_of_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
         "roofline": {"bound": "mfma", "achieved": round(kern_tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(kern_tflops / PEAK_BF16_TFLOPS, 4), "traffic": FFN_TRAFFIC_BYTES,

@@ -199,3 +199,18 @@ def test_reshard_validates_before_touching_the_gpu():
         with pytest.raises(g.GspmdError) as e:
             g.reshard(*args)
         assert e.value.status == status, args
+
+
+def test_flop_accounting_useful_and_padded():
+    import workloads as wl
+    # config 1: 90 columns over 4 partitions are 4 static shards of 23 (92 columns of work, 90 useful)
+    w = wl.tiny_1d()
+    assert w.useful_flops() == 2 * 8 * 90 * 64 and w.padded_flops() == 2 * 8 * 92 * 64
+    # the MoE share: useful flops count the occupied slots, padded flops the whole capacity
+    w = wl.moe()
+    fill = w.draw_fill()
+    assert w.useful_flops(fill) == 2.0 * float(fill.sum()) * 8192 * 32768
+    assert w.padded_flops() == 2.0 * 4 * 1024 * 8192 * 32768
+    # 5998 x 9999 over a 4 x 8 mesh: static shards of 1500 x 1250
+    w = wl.mesh2d_uneven()
+    assert w.useful_flops() == 2.0 * 5998 * 9999 * 12288 and w.padded_flops() == 2.0 * 6000 * 10000 * 12288

@@ -167,6 +167,21 @@ class DotWorkload:
             return 2.0 * float(np.sum(fill)) * rest
         return 2.0 * float(np.prod(out)) * k
 
+    def padded_flops(self) -> float:
+        """2 * (output elements) * K over the STATIC shard shapes: every split dimension rounded up to a multiple of its
+        mesh dimension, capacity slots counted whether occupied or not -- the convention of a profiler that counts
+        padded compute as valid compute (Section 5.2)."""
+        def padded(size: int, mesh_dim: int) -> int:
+            n = self.mesh_shape[mesh_dim] if mesh_dim >= 0 else 1
+            return n * (-(-size // n))
+        k = 1
+        for d in self.lhs_contract:
+            k *= padded(self.lhs_shape[d], self.lhs_map[d])
+        out = 1
+        for size, mesh_dim in zip(self.out_shape, self.out_map):
+            out *= padded(size, mesh_dim)
+        return 2.0 * float(out) * float(k)
+
 
 def _ids(n: int) -> Tuple[int, ...]:
     return tuple(range(n))
