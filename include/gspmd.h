@@ -17,8 +17,8 @@
  *     is the default stream) and is complete when that stream is.
  *   - Every function returns a gspmd_status and never throws (a failed host allocation comes back as
  *     GSPMD_ERR_HOST_MEMORY), aborts or prints.  Outputs are written only on GSPMD_OK.
- *   - The library keeps no state between calls (gspmd_grouped_dot_noalloc's static workspace aside); independent
- *     calls may be made from several host threads.
+ *   - The library keeps no state between calls (gspmd_grouped_dot_noalloc's static workspace and the profiling switch
+ *     of gspmd_set_tile_timeline aside); independent calls may be made from several host threads.
  *   - HIP graphs: a kernel-launching call whose launch tables fit its kernels' arguments enqueues kernels only and
  *     may be recorded into a graph: a Dot lowered to at most 32 GEMM problems (every benchmark configuration; the
  *     count is what gspmd_plan_dot reports, summed over the partitions of a grouped call), a resharding on a mesh of
@@ -340,8 +340,8 @@ int32_t gspmd_resharded_dot(const gspmd_mesh* mesh, const gspmd_dot_dims* dims,
  * the last to arrive) leaves words 5 to 7 untouched.  device_records: device memory of n_records * 64 bytes, 8-byte
  * aligned, owned by the caller, who clears it and keeps it alive until the launches have finished;
  * NULL or n_records 0 switches the timeline off (the default; the kernel then skips the stamps on one uniform branch).
- * The setting is process-wide, not per stream: launches that overlap write to the same records.  Results of the Dot
- * are unchanged.  Returns GSPMD_ERR_BAD_BUFFER for a misaligned pointer or a count outside [0, 2^31). */
+ * The setting is process-wide, not per stream: launches that overlap write to the same records, and a launch recorded
+ * into a HIP graph keeps the buffer it was recorded with.  Results of the Dot are unchanged.  Returns GSPMD_ERR_BAD_BUFFER for a misaligned pointer or a count outside [0, 2^31). */
 int32_t gspmd_set_tile_timeline(void* device_records, int64_t n_records);
 
 #ifdef __cplusplus
