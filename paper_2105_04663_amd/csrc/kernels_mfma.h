@@ -98,7 +98,7 @@ __device__ __forceinline__ void zero_rows_below(TOut* __restrict__ C, int ldc, i
     const u32x4_t z = {0u, 0u, 0u, 0u};
     for (int i = t; i < total; i += kMfmaThreads) {
       const int r = i / per_row, c = (i - r * per_row) * kPer;
-      *(global_u32x4_t*)(C + static_cast<int64_t>(row_begin + r) * ldc + col_begin + c) = z;
+      __builtin_nontemporal_store(z, (global_u32x4_t*)(C + static_cast<int64_t>(row_begin + r) * ldc + col_begin + c));
     }
   } else {
     const int total = (row_end - row_begin) * width;
