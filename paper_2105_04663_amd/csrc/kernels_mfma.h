@@ -517,16 +517,19 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const InlineProb
     constexpr int kPer = 16 / static_cast<int>(sizeof(TOut));
     zero_rows_below<TOut>(Cg, P.ldc, m_write_end, rows_cleared(P.Mv, P.Ms), n0, col_end, vec_ok && rows_16b && ((col_end - n0) % kPer) == 0, t);
   }
-  if (vec_ok && rows_16b && n0 + kMfmaBN <= P.Nv) {
-    // all 256 columns valid: whole 16-byte stores, predicated by row only; bf16 through the hardware
-    // round-to-nearest-even conversion
+  if (vec_ok && rows_16b) {
+    // 16-byte stores of whole lines; bf16 through the hardware round-to-nearest-even conversion.  A tile with all 256
+    // columns (and rows) valid stores without predicates; in the last tile column a lane's 16 bytes are masked beyond
+    // the valid columns, and the chunk that the static block ends in (if it ends inside one) is stored element by
+    // element, so that nothing is written beyond the block's static width.
     // Relu or not is decided once per workgroup, not per element: with the test inside the conversion loop the compiler
     // turns every element into a compare, a select and a repack.  Stores go through global-address-space pointers
     // (a flat store also counts as an LDS operation, and the waits for the staging reads would wait for it) with the
     // non-temporal hint (the output is written once and not read again by this launch; with 2 GB of output per launch
     // the hint is worth 8 %); all of a wave's staging reads are issued before its first store.
     const bool relu = epilogue == GSPMD_EPILOGUE_RELU;
-    const bool whole = rows_own >= kMfmaBM;          // all 256 rows valid: no row predicates
+    const bool all_cols = n0 + kMfmaBN <= P.Nv;
+    const bool whole = rows_own >= kMfmaBM && all_cols;          // all 256 rows and columns valid: no predicates
     if constexpr (sizeof(TOut) == 2) {
       // bf16: the wave's 128 x 64 block is a 128-byte line per row, but a lane holds only 8 bytes of it per 16-column
       // block.  Stage it through the wave's own slice of LDS (free now: every wave's LDS reads are over and no tile load is in flight;
@@ -557,12 +560,29 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const InlineProb
       if (whole) {
 #pragma unroll
         for (int p = 0; p < 16; ++p) __builtin_nontemporal_store(v[p], &c0[p * pitch8]);
-      } else {
+      } else if (all_cols) {
 #pragma unroll
         for (int p = 0; p < 16; ++p) {
           const int row = row0 + p * 8;
           if (row >= rows_own) v[p] = u32x4_t{0u, 0u, 0u, 0u};
           if (row < rows_write) __builtin_nontemporal_store(v[p], &c0[p * pitch8]);
+        }
+      } else {
+        const int col = n0 + wn * 64 + (lane & 7) * 8;                         // this lane's 8 columns
+        const int keep = max(0, min(8, P.Nv - col)), room = max(0, min(8, P.Ns - col));
+#pragma unroll
+        for (int p = 0; p < 16; ++p) {
+          const int row = row0 + p * 8;
+          const u32x4_t o = row < rows_own ? mask_tail8(v[p], keep) : u32x4_t{0u, 0u, 0u, 0u};
+          if (row >= rows_write) continue;
+          if (room == 8) {
+            __builtin_nontemporal_store(o, &c0[p * pitch8]);
+          } else {
+            bf16_bits* out = reinterpret_cast<bf16_bits*>(Cg) + static_cast<int64_t>(m0 + row) * P.ldc + col;
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+              if (e < room) out[e] = static_cast<bf16_bits>(o[e >> 1] >> ((e & 1) * 16));
+          }
         }
       }
     } else {
@@ -595,12 +615,32 @@ __global__ __launch_bounds__(kMfmaThreads) void dot_mfma_kernel(const InlineProb
         if (whole) {
 #pragma unroll
           for (int i = 0; i < 16; ++i) __builtin_nontemporal_store(v[i], &c0[(pass * 16 + i) * pitch4]);
-        } else {
+        } else if (all_cols) {
 #pragma unroll
           for (int i = 0; i < 16; ++i) {
             const int row = wm * 128 + pass * 64 + i * 4 + (lane >> 4);
             if (row >= rows_own) v[i] = u32x4_t{0u, 0u, 0u, 0u};
             if (row < rows_write) __builtin_nontemporal_store(v[i], &c0[(pass * 16 + i) * pitch4]);
+          }
+        } else {
+          const int col = n0 + wn * 64 + (lane & 15) * 4;                      // this lane's 4 columns
+          const int keep = max(0, min(4, P.Nv - col)), room = max(0, min(4, P.Ns - col));
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const int row = wm * 128 + pass * 64 + i * 4 + (lane >> 4);
+            u32x4_t o = v[i];
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (row >= rows_own || e >= keep) o[e] = 0u;
+            if (row >= rows_write) continue;
+            if (room == 4) {
+              __builtin_nontemporal_store(o, &c0[(pass * 16 + i) * pitch4]);
+            } else {
+              uint32_t* out = reinterpret_cast<uint32_t*>(Cg) + static_cast<int64_t>(m0 + row) * P.ldc + col;
+#pragma unroll
+              for (int e = 0; e < 4; ++e)
+                if (e < room) out[e] = o[e];
+            }
           }
         }
       }
