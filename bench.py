@@ -412,6 +412,17 @@ def main():
                    "under_load": under_load},
     }
 
+    if under_load and under_load.get("sclk_mhz"):
+        # Clock-normalised view, so that a kernel change can be told from a faster or slower box: shader cycles a
+        # compute unit spends per 64-wide K step of one 256 x 256 tile (2048 of them would be back-to-back MFMAs), and the
+        # fraction of the peak AT THE SAMPLED CLOCK.  The clock is sampled outside the timed region, under the same load.
+        tiles_per_cu = (16384 // 256) * (8192 // 256) / prop.multi_processor_count
+        k_steps = 8192 // 64
+        clk = under_load["sclk_mhz"] * 1e6
+        result["roofline"]["sclk_mhz_under_load"] = under_load["sclk_mhz"]
+        result["roofline"]["shader_cycles_per_k_step"] = round(ev_ms * 1e-3 * clk / (tiles_per_cu * k_steps), 1)
+        result["roofline"]["frac_at_sampled_clock"] = round(kern_tflops * 1e12 / (prop.multi_processor_count * 4096 * clk), 4)
+
     # ------------------------------------------------------------------ CPU oracle on a row sample
     if not args.headline_only:
         from oracle import dot as od
